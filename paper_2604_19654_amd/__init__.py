@@ -1,0 +1,11 @@
+"""MI355X-native single-rank MoE hot path of FEPLB: a thin ctypes binding over
+libfeplb.so (hand-written HIP kernels behind a C ABI, see include/feplb.h)."""
+from .binding import (  # noqa: F401
+    FeplbError, Group, Move, ORD_MAX, F32, BF16, FFN_GATE_UP, FFN_DOWN, FFN_SCHEDULE, FFN_ALL,
+    PLAN_WHOLE, PLAN_OVERFLOW, lib, lib_path, version, HipEvent,
+    feplb_route_topk, feplb_permute, feplb_permute_workspace_bytes,
+    feplb_grouped_ffn, feplb_grouped_ffn_workspace_bytes,
+    feplb_unpermute_combine, feplb_stage_weights, feplb_stream_wait,
+    feplb_expert_bytes, feplb_plan,
+)
+from .layer import RankLayer, LayerBuffers  # noqa: F401

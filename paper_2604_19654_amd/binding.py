@@ -1,0 +1,298 @@
+"""ctypes binding of libfeplb.so.  Argument marshalling only: every step of the
+path runs in the library's HIP kernels (or, for the plan, its host C++).  Torch
+tensors provide device memory and streams; nothing here computes.
+
+The library must have been built (python -m paper_2604_19654_amd.build, or
+__graft_entry__.build()); loading fails loudly otherwise -- there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ORD_MAX = 2**31 - 1
+F32, BF16 = 0, 1
+FFN_GATE_UP, FFN_DOWN, FFN_SCHEDULE, FFN_ALL = 1, 2, 4, 7
+PLAN_WHOLE, PLAN_OVERFLOW = 0, 1
+
+
+class FeplbError(RuntimeError):
+    pass
+
+
+class Group(C.Structure):
+    _fields_ = [("expert", C.c_int32), ("ord_lo", C.c_int32), ("ord_hi", C.c_int32)]
+
+
+class Move(C.Structure):
+    _fields_ = [("expert", C.c_int32), ("src", C.c_int32), ("dst", C.c_int32),
+                ("reserved", C.c_int32), ("rows", C.c_int64), ("ord_lo", C.c_int64)]
+
+
+_LIB = None
+
+
+def lib_path() -> str:
+    return os.path.join(HERE, "libfeplb.so")
+
+
+def lib():
+    global _LIB
+    if _LIB is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise FeplbError(f"{path} is missing: build it with `python -m paper_2604_19654_amd.build`")
+        L = C.CDLL(path)
+        vp, i32, sz, i64 = C.c_void_p, C.c_int32, C.c_size_t, C.c_int64
+        L.feplb_version.restype = C.c_char_p
+        L.feplb_last_error.restype = C.c_char_p
+        L.feplb_route_topk.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp]
+        L.feplb_permute_workspace_bytes.argtypes = [i32, i32, i32, i32]
+        L.feplb_permute_workspace_bytes.restype = sz
+        L.feplb_permute.argtypes = [vp, i32, i32, i32, C.POINTER(Group), i32, vp, i32, vp, i32,
+                                    vp, vp, vp, vp, sz, vp]
+        L.feplb_grouped_ffn_workspace_bytes.argtypes = [i32, i32]
+        L.feplb_grouped_ffn_workspace_bytes.restype = sz
+        L.feplb_grouped_ffn.argtypes = [vp, vp, i32, i32, i32, i32, i32, C.POINTER(vp), C.POINTER(vp),
+                                        C.POINTER(vp), vp, vp, i32, i32, vp, sz, vp]
+        L.feplb_unpermute_combine.argtypes = [vp, i32, vp, vp, i32, i32, i32, vp, vp]
+        L.feplb_stage_weights.argtypes = [vp, vp, sz, vp, vp]
+        L.feplb_stream_wait.argtypes = [vp, vp]
+        L.feplb_expert_bytes.argtypes = [i32, i32, i32]
+        L.feplb_expert_bytes.restype = sz
+        L.feplb_plan.argtypes = [i32, i32, vp, vp, vp, vp, i64, i32, i32, C.POINTER(Move), i32,
+                                 C.POINTER(i32), vp, vp, C.POINTER(i32)]
+        for name in ("feplb_route_topk", "feplb_permute", "feplb_grouped_ffn", "feplb_unpermute_combine",
+                     "feplb_stage_weights", "feplb_stream_wait", "feplb_plan"):
+            getattr(L, name).restype = i32
+        _LIB = L
+    return _LIB
+
+
+_HIP = None
+
+
+def hip_runtime():
+    """The HIP runtime torch already loaded (so that streams and events are shared)."""
+    global _HIP
+    if _HIP is None:
+        path = None
+        with open("/proc/self/maps") as fh:
+            for line in fh:
+                if "libamdhip64" in line:
+                    path = line.split()[-1]
+                    break
+        _HIP = C.CDLL(path or "libamdhip64.so")
+        _HIP.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        _HIP.hipEventDestroy.argtypes = [C.c_void_p]
+        _HIP.hipEventRecord.argtypes = [C.c_void_p, C.c_void_p]
+        _HIP.hipEventSynchronize.argtypes = [C.c_void_p]
+        _HIP.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+    return _HIP
+
+
+class HipEvent:
+    """A plain hipEvent_t (timing enabled), recordable on any stream."""
+
+    def __init__(self):
+        self.handle = C.c_void_p()
+        rc = hip_runtime().hipEventCreate(C.byref(self.handle))
+        if rc != 0:
+            raise FeplbError(f"hipEventCreate failed: {rc}")
+
+    def record(self, stream=None):
+        rc = hip_runtime().hipEventRecord(self.handle, _stream(stream))
+        if rc != 0:
+            raise FeplbError(f"hipEventRecord failed: {rc}")
+
+    def synchronize(self):
+        rc = hip_runtime().hipEventSynchronize(self.handle)
+        if rc != 0:
+            raise FeplbError(f"hipEventSynchronize failed: {rc}")
+
+    def elapsed_ms(self, later: "HipEvent") -> float:
+        ms = C.c_float(0.0)
+        rc = hip_runtime().hipEventElapsedTime(C.byref(ms), self.handle, later.handle)
+        if rc != 0:
+            raise FeplbError(f"hipEventElapsedTime failed: {rc}")
+        return float(ms.value)
+
+    def __del__(self):
+        try:
+            if self.handle:
+                hip_runtime().hipEventDestroy(self.handle)
+        except Exception:
+            pass
+
+
+def version() -> str:
+    return lib().feplb_version().decode()
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise FeplbError(f"{what} failed with code {rc}: {lib().feplb_last_error().decode()}")
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise FeplbError("tensors passed to the library must be contiguous")
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def _need(t: torch.Tensor, dtype, name: str):
+    if not t.is_cuda or t.dtype != dtype:
+        raise FeplbError(f"{name}: expected a CUDA tensor of {dtype}, got {t.dtype} on {t.device}")
+
+
+def feplb_route_topk(logits, k, topk_ids=None, topk_w=None, counts=None, want_counts=True, stream=None):
+    """logits fp32 [T,E] -> (topk_ids int32 [T,k], topk_w fp32 [T,k], counts int32 [E] or None)."""
+    _need(logits, torch.float32, "logits")
+    T, E = logits.shape
+    dev = logits.device
+    if topk_ids is None:
+        topk_ids = torch.empty((T, k), dtype=torch.int32, device=dev)
+    if topk_w is None:
+        topk_w = torch.empty((T, k), dtype=torch.float32, device=dev)
+    if counts is None and want_counts:
+        counts = torch.empty((E,), dtype=torch.int32, device=dev)
+    _check(lib().feplb_route_topk(_ptr(logits), T, E, k, _ptr(topk_ids), _ptr(topk_w), _ptr(counts),
+                                  _stream(stream)), "feplb_route_topk")
+    return topk_ids, topk_w, counts
+
+
+def feplb_permute_workspace_bytes(T, k, E, G) -> int:
+    return int(lib().feplb_permute_workspace_bytes(T, k, E, G))
+
+
+def _group_array(groups: Sequence):
+    arr = (Group * max(len(groups), 1))()
+    for i, g in enumerate(groups):
+        e, lo, hi = (g.expert, g.ord_lo, g.ord_hi) if isinstance(g, Group) else g
+        arr[i] = Group(int(e), int(lo), int(hi))
+    return arr
+
+
+def feplb_permute(topk_ids, E, groups, X, R_cap, Xp=None, offsets=None, row_src=None, inv=None,
+                  ws=None, stream=None):
+    """-> (Xp bf16 [R_cap,d], offsets int32 [G+1], row_src int32 [R_cap], inv int32 [T*k])."""
+    _need(topk_ids, torch.int32, "topk_ids")
+    T, k = topk_ids.shape
+    G = len(groups)
+    dev = topk_ids.device
+    d = 0
+    if X is not None:
+        _need(X, torch.bfloat16, "X")
+        d = X.shape[1]
+        if Xp is None:
+            Xp = torch.empty((R_cap, d), dtype=torch.bfloat16, device=dev)
+    if offsets is None:
+        offsets = torch.empty((G + 1,), dtype=torch.int32, device=dev)
+    if row_src is None:
+        row_src = torch.empty((max(R_cap, 1),), dtype=torch.int32, device=dev)
+    if inv is None:
+        inv = torch.empty((max(T * k, 1),), dtype=torch.int32, device=dev)
+    need = feplb_permute_workspace_bytes(T, k, E, G)
+    if ws is None:
+        ws = torch.empty((need,), dtype=torch.uint8, device=dev)
+    _check(lib().feplb_permute(_ptr(topk_ids), T, k, E, _group_array(groups), G, _ptr(X), d, _ptr(Xp),
+                               R_cap, _ptr(offsets), _ptr(row_src), _ptr(inv), _ptr(ws), ws.numel(),
+                               _stream(stream)), "feplb_permute")
+    return Xp, offsets, row_src, inv
+
+
+def feplb_grouped_ffn_workspace_bytes(R_cap, G) -> int:
+    return int(lib().feplb_grouped_ffn_workspace_bytes(R_cap, G))
+
+
+def _ptr_array(tensors: Sequence[Optional[torch.Tensor]]):
+    arr = (C.c_void_p * max(len(tensors), 1))()
+    for i, t in enumerate(tensors):
+        arr[i] = None if t is None else (t if isinstance(t, int) else _ptr(t))
+    return arr
+
+
+def feplb_grouped_ffn(Xp, offsets, g_begin, g_end, d, f, w_gate, w_up, w_down, H, Yp,
+                      phases=FFN_ALL, ws=None, stream=None):
+    """Runs groups [g_begin, g_end).  w_* are sequences (indexed by group) of bf16
+    tensors or raw device addresses.  H bf16 [R_cap,f]; Yp fp32 or bf16 [R_cap,d]."""
+    R_cap = H.shape[0]
+    yp_dtype = F32
+    if Yp is not None:
+        yp_dtype = {torch.float32: F32, torch.bfloat16: BF16}[Yp.dtype]
+    if ws is None:
+        ws = torch.empty((feplb_grouped_ffn_workspace_bytes(R_cap, g_end),), dtype=torch.uint8,
+                         device=H.device)
+    _check(lib().feplb_grouped_ffn(_ptr(Xp), _ptr(offsets), g_begin, g_end, R_cap, d, f,
+                                   _ptr_array(w_gate), _ptr_array(w_up), _ptr_array(w_down),
+                                   _ptr(H), _ptr(Yp), yp_dtype, phases, _ptr(ws), ws.numel(),
+                                   _stream(stream)), "feplb_grouped_ffn")
+    return H, Yp
+
+
+def feplb_unpermute_combine(Yp, inv, topk_w, T, k, d, Y=None, stream=None):
+    """-> Y bf16 [T,d]."""
+    yp_dtype = {torch.float32: F32, torch.bfloat16: BF16}[Yp.dtype]
+    if Y is None:
+        Y = torch.empty((T, d), dtype=torch.bfloat16, device=Yp.device)
+    _check(lib().feplb_unpermute_combine(_ptr(Yp), yp_dtype, _ptr(inv), _ptr(topk_w), T, k, d, _ptr(Y),
+                                         _stream(stream)), "feplb_unpermute_combine")
+    return Y
+
+
+def feplb_stage_weights(slot: torch.Tensor, src: torch.Tensor, side_stream, done_event: "HipEvent" = None):
+    """Async copy src -> slot on side_stream; records done_event there if given."""
+    nbytes = src.numel() * src.element_size()
+    if slot.numel() * slot.element_size() < nbytes:
+        raise FeplbError("staging slot smaller than the source")
+    _check(lib().feplb_stage_weights(_ptr(slot), _ptr(src), nbytes, _stream(side_stream),
+                                     done_event.handle if done_event is not None else None),
+           "feplb_stage_weights")
+
+
+def feplb_stream_wait(stream, event: "HipEvent"):
+    _check(lib().feplb_stream_wait(_stream(stream), event.handle), "feplb_stream_wait")
+
+
+def feplb_expert_bytes(d, f, elem_bytes=2) -> int:
+    return int(lib().feplb_expert_bytes(d, f, elem_bytes))
+
+
+def feplb_plan(P, owner, n, dyn_flag, slots, tau=0, mode=PLAN_WHOLE, this_rank=-1, max_moves=None):
+    """Host-only.  Returns (moves [(expert, src, dst, rows, ord_lo)], load_before, load_after, chosen_rank)."""
+    owner = np.ascontiguousarray(owner, dtype=np.int32)
+    n = np.ascontiguousarray(n, dtype=np.int64)
+    dyn_flag = np.ascontiguousarray(dyn_flag, dtype=np.uint8)
+    slots = np.ascontiguousarray(slots, dtype=np.int32)
+    E = int(n.shape[0])
+    if owner.shape[0] != E or dyn_flag.shape[0] != E or slots.shape[0] != P:
+        raise FeplbError("feplb_plan: array lengths do not match P/E")
+    if max_moves is None:
+        max_moves = int(slots.sum()) if mode == PLAN_WHOLE else int(slots[this_rank] if this_rank >= 0 else slots.max(initial=0))
+        max_moves = max(max_moves, 1)
+    moves = (Move * max_moves)()
+    n_moves = C.c_int32(0)
+    chosen = C.c_int32(-1)
+    before = np.zeros(P, dtype=np.int64)
+    after = np.zeros(P, dtype=np.int64)
+    _check(lib().feplb_plan(P, E, owner.ctypes.data, n.ctypes.data, dyn_flag.ctypes.data,
+                            slots.ctypes.data, int(tau), int(mode), int(this_rank), moves, max_moves,
+                            C.byref(n_moves), before.ctypes.data, after.ctypes.data, C.byref(chosen)),
+           "feplb_plan")
+    out = [(m.expert, m.src, m.dst, int(m.rows), int(m.ord_lo)) for m in moves[: n_moves.value]]
+    return out, before, after, chosen.value

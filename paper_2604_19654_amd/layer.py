@@ -1,0 +1,157 @@
+"""One EP rank's MoE layer as a sequence of library calls (paper Section 2.3,
+per-micro-batch timeline): route -> [counts to host -> plan -> stage dynamic
+experts' weights on a side stream] -> permute -> static experts' FFN ->
+wait for the staging event -> dynamic experts' FFN -> combine.
+
+Only sequencing, buffer ownership and stream plumbing live here; every step is
+a call into libfeplb.so.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+@dataclass
+class LayerBuffers:
+    topk_ids: torch.Tensor
+    topk_w: torch.Tensor
+    counts: torch.Tensor
+    counts_host: torch.Tensor
+    offsets: torch.Tensor
+    row_src: torch.Tensor
+    inv: torch.Tensor
+    Xp: torch.Tensor
+    H: torch.Tensor
+    Yp: torch.Tensor
+    Y: torch.Tensor
+    ws_permute: torch.Tensor
+    ws_ffn: torch.Tensor
+    slots: Optional[torch.Tensor]
+
+
+class RankLayer:
+    """Pre-allocates every buffer once (sized by R_cap rows and G_cap groups) so
+    that a step launches kernels only."""
+
+    def __init__(self, T, E, k, d, f, R_cap, G_cap, device="cuda", yp_dtype=torch.float32, n_slots=0):
+        self.T, self.E, self.k, self.d, self.f = T, E, k, d, f
+        self.R_cap, self.G_cap, self.n_slots = R_cap, G_cap, n_slots
+        dev = torch.device(device)
+        i32 = dict(dtype=torch.int32, device=dev)
+        bf = dict(dtype=torch.bfloat16, device=dev)
+        self.expert_elems = 3 * d * f
+        self.buf = LayerBuffers(
+            topk_ids=torch.empty((T, k), **i32),
+            topk_w=torch.empty((T, k), dtype=torch.float32, device=dev),
+            counts=torch.empty((E,), **i32),
+            counts_host=torch.empty((E,), dtype=torch.int32, pin_memory=True),
+            offsets=torch.zeros((G_cap + 1,), **i32),
+            row_src=torch.empty((max(R_cap, 1),), **i32),
+            inv=torch.empty((max(T * k, 1),), **i32),
+            Xp=torch.empty((R_cap, d), **bf),
+            H=torch.empty((R_cap, f), **bf),
+            Yp=torch.empty((R_cap, d), dtype=yp_dtype, device=dev),
+            Y=torch.empty((T, d), **bf),
+            ws_permute=torch.empty((B.feplb_permute_workspace_bytes(T, k, E, G_cap),), dtype=torch.uint8, device=dev),
+            ws_ffn=torch.empty((B.feplb_grouped_ffn_workspace_bytes(R_cap, G_cap),), dtype=torch.uint8, device=dev),
+            slots=torch.empty((n_slots, self.expert_elems), **bf) if n_slots else None,
+        )
+        self.side_stream = torch.cuda.Stream(device=dev) if n_slots else None
+        self.staged = B.HipEvent() if n_slots else None
+        self.timeline: Dict[str, B.HipEvent] = {}
+
+    # -- helpers ---------------------------------------------------------
+    def _mark(self, name: str, on: bool):
+        if on:
+            ev = self.timeline.get(name)
+            if ev is None:
+                ev = self.timeline[name] = B.HipEvent()
+            ev.record(None)
+
+    def slot_views(self, i: int):
+        d, f = self.d, self.f
+        s = self.buf.slots[i]
+        return s[: d * f].view(d, f), s[d * f: 2 * d * f].view(d, f), s[2 * d * f:].view(f, d)
+
+    # -- static-only layer (no dynamic experts) ---------------------------
+    def forward(self, logits, X, groups: Sequence[Tuple[int, int, int]], weights: Sequence[Tuple], mark=False):
+        """groups[g] = (expert, ord_lo, ord_hi); weights[g] = (W_gate, W_up, W_down). Returns Y."""
+        b = self.buf
+        G = len(groups)
+        self._mark("start", mark)
+        B.feplb_route_topk(logits, self.k, b.topk_ids, b.topk_w, b.counts)
+        self._mark("routed", mark)
+        B.feplb_permute(b.topk_ids, self.E, groups, X, self.R_cap, b.Xp, b.offsets[: G + 1], b.row_src, b.inv,
+                        b.ws_permute)
+        self._mark("permuted", mark)
+        wg, wu, wd = ([w[i] for w in weights] for i in range(3))
+        B.feplb_grouped_ffn(b.Xp, b.offsets, 0, G, self.d, self.f, wg, wu, wd, b.H, b.Yp,
+                            phases=B.FFN_SCHEDULE, ws=b.ws_ffn)
+        self._mark("scheduled", mark)
+        B.feplb_grouped_ffn(b.Xp, b.offsets, 0, G, self.d, self.f, wg, wu, wd, b.H, b.Yp,
+                            phases=B.FFN_GATE_UP, ws=b.ws_ffn)
+        self._mark("gate_up_done", mark)
+        B.feplb_grouped_ffn(b.Xp, b.offsets, 0, G, self.d, self.f, wg, wu, wd, b.H, b.Yp,
+                            phases=B.FFN_DOWN, ws=b.ws_ffn)
+        self._mark("down_done", mark)
+        B.feplb_unpermute_combine(b.Yp, b.inv, b.topk_w, self.T, self.k, self.d, b.Y)
+        self._mark("combined", mark)
+        return b.Y
+
+    # -- rebalanced layer: static experts + replicas of the hottest foreign experts
+    def forward_rebalanced(self, logits, X, P, owner, dyn_flag, slots, this_rank,
+                           static_weights: Dict[int, Tuple], remote_sources: Dict[int, torch.Tensor],
+                           mark=False, overlap=True):
+        """The rank runs its own experts as the static range and `slots[this_rank]`
+        replicas as the dynamic range.  remote_sources[e] is one contiguous bf16
+        tensor [gate | up | down] of expert e living where the copy engine reads it
+        (another device buffer or pinned host memory).  Returns (Y, info)."""
+        b = self.buf
+        main = torch.cuda.current_stream()
+        self._mark("start", mark)
+        B.feplb_route_topk(logits, self.k, b.topk_ids, b.topk_w, b.counts)
+        self._mark("routed", mark)
+        # per-expert counts to the host: the plan is CPU work triggered by the router (Section 2.3)
+        b.counts_host.copy_(b.counts, non_blocking=True)
+        main.synchronize()
+        n = b.counts_host.numpy().astype(np.int64)
+        moves, before, after, rank = B.feplb_plan(P, owner, n, dyn_flag, slots, 0, B.PLAN_OVERFLOW, this_rank)
+        per = self.E // P
+        static = list(range(rank * per, (rank + 1) * per))
+        groups = [(e, 0, B.ORD_MAX) for e in static]
+        groups += [(e, lo, lo + rows) for (e, _src, _dst, rows, lo) in moves]
+        Gs, G = len(static), len(static) + len(moves)
+        if len(moves) > self.n_slots:
+            raise B.FeplbError("more replicas than staging slots")
+        # weights of the replicas: copy engine, side stream, off the compute units
+        side = self.side_stream if overlap else main
+        if overlap:
+            side.wait_stream(main)
+        for i, (e, *_rest) in enumerate(moves):
+            last = i == len(moves) - 1
+            B.feplb_stage_weights(b.slots[i], remote_sources[e], side, self.staged if last else None)
+        B.feplb_permute(b.topk_ids, self.E, groups, X, self.R_cap, b.Xp, b.offsets[: G + 1], b.row_src, b.inv,
+                        b.ws_permute)
+        self._mark("permuted", mark)
+        wlist = [static_weights[e] for e in static] + [self.slot_views(i) for i in range(len(moves))]
+        wg, wu, wd = ([w[i] for w in wlist] for i in range(3))
+        both = B.FFN_ALL
+        B.feplb_grouped_ffn(b.Xp, b.offsets, 0, Gs, self.d, self.f, wg, wu, wd, b.H, b.Yp, phases=both,
+                            ws=b.ws_ffn)
+        self._mark("static_done", mark)
+        if moves:
+            B.feplb_stream_wait(main, self.staged)
+            self._mark("staged", mark)
+            B.feplb_grouped_ffn(b.Xp, b.offsets, Gs, G, self.d, self.f, wg, wu, wd, b.H, b.Yp, phases=both,
+                                ws=b.ws_ffn)
+        self._mark("dynamic_done", mark)
+        B.feplb_unpermute_combine(b.Yp, b.inv, b.topk_w, self.T, self.k, self.d, b.Y)
+        self._mark("combined", mark)
+        info = dict(rank=rank, moves=moves, groups=groups, load_before=before, load_after=after, n=n)
+        return b.Y, info

@@ -1,0 +1,31 @@
+"""Helpers shared by the tests: tensor -> float64 arrays, the float tolerance."""
+import numpy as np
+import torch
+
+
+def f64(t: torch.Tensor) -> np.ndarray:
+    """Exact widening of a (bf16 / fp32) tensor to a float64 NumPy array on the host."""
+    return t.detach().to("cpu").to(torch.float64).numpy()
+
+
+def i64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to("cpu").numpy()
+
+
+# Float bar of the build: max-abs-err <= 2e-2 relative to output RMS for bf16 with
+# fp32 accumulation, read per token row against the unrounded float64 oracle
+# (a row's scale is set by its combine weights, so one global RMS would put the
+# bound below the bf16 rounding step of the largest rows).
+ROW_TOL = 2e-2
+
+
+def row_rel_err(got: np.ndarray, want: np.ndarray) -> np.ndarray:
+    """max_i |got - want| / rms_i(want) per row; rows whose oracle value is all
+    zero must match exactly (reported as 0 or inf)."""
+    err = np.abs(got - want).max(axis=1)
+    rms = np.sqrt((want ** 2).mean(axis=1))
+    out = np.zeros_like(err)
+    nz = rms > 0
+    out[nz] = err[nz] / rms[nz]
+    out[~nz] = np.where(err[~nz] == 0, 0.0, np.inf)
+    return out
