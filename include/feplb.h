@@ -97,7 +97,7 @@ int32_t feplb_route_topk(const float* logits, int32_t T, int32_t E, int32_t k,
  * If R > R_cap, rows beyond R_cap are not written (offsets and inv still hold
  * the true values, so the caller can detect the overflow from offsets[G]).
  * Limits: d % 8 == 0, G <= FEPLB_MAX_GROUPS, E <= FEPLB_MAX_EXPERTS, T*k < 2^31.
- * X and Xp may be NULL together to compute the index arrays only.
+ * With Xp NULL only the index arrays are computed (X is then ignored).
  */
 typedef struct feplb_group {
   int32_t expert;

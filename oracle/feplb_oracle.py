@@ -20,7 +20,7 @@ What each function follows:
   ffn_rows, grouped_ffn   Section 3.1 (expert compute is a grouped GEMM);
                     the expert is a SwiGLU MLP without biases.
   combine           Section 2.3 (combine returns expert outputs to tokens).
-  moe_token         the layer's definition for one token, no permutation.
+  moe_token, moe_tokens   the layer's definition per token, no permutation.
   plan_whole        Section 2.3, the greedy whole-expert balancer.
   plan_overflow     NOT in the paper (which never splits an expert's batch):
                     the replicate-the-hottest rule of the rebalanced workload.
@@ -167,6 +167,25 @@ def moe_token(x_t: np.ndarray, ids_t, w_t, expert_weights: dict) -> np.ndarray:
         if e in expert_weights:
             y += float(w_t[j]) * ffn_rows(x, *expert_weights[e])[1][0]
     return y
+
+
+def moe_tokens(x_rows: np.ndarray, ids_rows, w_rows, keep_rows, weights_of) -> np.ndarray:
+    """moe_token for a batch of tokens, visiting one expert at a time so that
+    each expert's matrices are widened to float64 once.  keep_rows [m,k] marks
+    the slots that are local (inv >= 0); for every expert e that occurs in a
+    kept slot, the rows whose kept slot j names e get w_j * FFN_e(x) added.
+    `weights_of(e)` returns (Wg, Wu, Wd).  Same sums as moe_token."""
+    x = np.asarray(x_rows, dtype=np.float64)
+    ids_rows = np.asarray(ids_rows)
+    keep_rows = np.asarray(keep_rows, dtype=bool)
+    w_rows = np.asarray(w_rows, dtype=np.float64)
+    out = np.zeros_like(x)
+    for e in sorted(set(int(v) for v in ids_rows[keep_rows])):
+        tok, slot = np.nonzero((ids_rows == e) & keep_rows)
+        y = ffn_rows(x[tok], *weights_of(e))[1]
+        for i in range(tok.size):
+            out[tok[i]] += w_rows[tok[i], slot[i]] * y[i]
+    return out
 
 
 # --------------------------------------------------------------------------

@@ -39,7 +39,10 @@ __global__ __launch_bounds__(BLOCK) void combine_kernel(const void* __restrict__
     my_w = w[t * k + lane];
   }
   u32x4* out = Y + t * nvec;
-  for (int v = lane; v < nvec; v += 64) {
+  // the loop bound is uniform so that every lane takes part in the broadcasts
+  for (int v0 = 0; v0 < nvec; v0 += 64) {
+    const int v = v0 + lane;
+    const bool live = v < nvec;
     float acc[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = 0.f;
@@ -47,6 +50,7 @@ __global__ __launch_bounds__(BLOCK) void combine_kernel(const void* __restrict__
       const int r = __shfl(my_row, j, 64);
       if (r < 0) continue;  // uniform across the wave
       const float wj = __shfl(my_w, j, 64);
+      if (!live) continue;
       if (YP_BF16) {
         const u32x4 p = ((const u32x4*)Yp)[(long long)r * nvec + v];
 #pragma unroll
@@ -69,7 +73,7 @@ __global__ __launch_bounds__(BLOCK) void combine_kernel(const void* __restrict__
     o[1] = pack2(acc[2], acc[3]);
     o[2] = pack2(acc[4], acc[5]);
     o[3] = pack2(acc[6], acc[7]);
-    out[v] = o;
+    if (live) out[v] = o;
   }
 }
 

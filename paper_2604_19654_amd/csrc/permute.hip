@@ -258,9 +258,8 @@ extern "C" int32_t feplb_permute(const int32_t* topk_ids, int32_t T, int32_t k, 
   FEPLB_REQUIRE(groups || G == 0, FEPLB_EINVAL, "permute: null groups");
   FEPLB_REQUIRE((topk_ids && inv) || A == 0, FEPLB_EINVAL, "permute: null ids/inv");
   FEPLB_REQUIRE(row_src || R_cap == 0, FEPLB_EINVAL, "permute: null row_src");
-  FEPLB_REQUIRE((X == nullptr) == (Xp == nullptr), FEPLB_EINVAL,
-                "permute: X and Xp must be given together");
-  if (X) {
+  FEPLB_REQUIRE(X || !Xp || A == 0 || d == 0, FEPLB_EINVAL, "permute: Xp given without X");
+  if (X && Xp) {
     FEPLB_REQUIRE(d % 8 == 0, FEPLB_ESHAPE, "permute: d=%d not a multiple of 8", d);
     FEPLB_REQUIRE(feplb::aligned16(X) && feplb::aligned16(Xp), FEPLB_EALIGN,
                   "permute: X/Xp not 16-byte aligned");
@@ -307,7 +306,7 @@ extern "C" int32_t feplb_permute(const int32_t* topk_ids, int32_t T, int32_t k, 
                        L.nchunks, hist, meta, R_cap, row_src, inv);
     FEPLB_LAUNCH_CHECK("assign_rows_kernel");
   }
-  if (X && R_cap > 0 && d > 0) {
+  if (X && Xp && R_cap > 0 && d > 0) {
     const int blocks = (R_cap + WAVES - 1) / WAVES;
     hipLaunchKernelGGL(gather_rows_kernel, dim3(blocks), dim3(BLOCK), 0, s, (const u32x4*)X,
                        row_src, offsets, G, k, d / 8, R_cap, (u32x4*)Xp);

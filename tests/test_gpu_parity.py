@@ -1,0 +1,382 @@
+"""Parity of the HIP path with the CPU oracle, element by element, through the
+C ABI (ctypes binding).  Integer outputs must be bit-exact; float outputs must
+stay within ROW_TOL (tests/util.py).  Needs an MI355X: run with -m gpu."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2604_19654_amd as fe
+from paper_2604_19654_amd import runner
+import workloads
+from oracle import feplb_oracle as orc
+from tests.util import f64, row_rel_err, bf16_rounding_excess, ROW_TOL
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+# ------------------------------------------------------------------ routing
+@pytest.mark.parametrize("T,E,k", [(512, 8, 2), (1000, 128, 8), (77, 5, 5), (300, 64, 1), (129, 200, 6),
+                                   (64, 1024, 32), (33, 16, 16), (1, 128, 8), (4099, 128, 8), (257, 3, 2)])
+def test_route_topk_parity(T, E, k):
+    say(f"route T={T} E={E} k={k}")
+    g = torch.Generator().manual_seed(T * 31 + E)
+    logits = torch.randn((T, E), generator=g)
+    # plant ties (equal values, and +0 / -0) so that the tie-break is exercised
+    if E >= 4 and T >= 8:
+        logits[1, :] = 0.5
+        logits[2, : E // 2] = logits[2, E // 2: 2 * (E // 2)]
+        logits[3, 0] = 0.0
+        logits[3, 1] = -0.0
+        logits[3, 2:] = -1.0
+        logits[5, :] = torch.round(logits[5, :] * 2) / 2
+    ids, w, counts = fe.feplb_route_topk(logits.to(DEV), k)
+    torch.cuda.synchronize()
+    oid, ow, oc = orc.route_topk(logits.numpy(), k)
+    assert np.array_equal(ids.cpu().numpy(), oid)
+    assert np.array_equal(counts.cpu().numpy(), oc)
+    wg = w.cpu().numpy().astype(np.float64)
+    assert np.abs(wg - ow).max() <= 1e-6
+    assert np.abs(wg.sum(axis=1) - 1.0).max() <= 1e-6
+
+
+def test_route_topk_empty_and_no_counts():
+    logits = torch.zeros((0, 16), device=DEV)
+    ids, w, counts = fe.feplb_route_topk(logits, 4)
+    torch.cuda.synchronize()
+    assert ids.shape == (0, 4) and counts.cpu().tolist() == [0] * 16
+    logits = torch.randn((40, 16), generator=torch.Generator().manual_seed(1))
+    ids, w, counts = fe.feplb_route_topk(logits.to(DEV), 4, want_counts=False)
+    torch.cuda.synchronize()
+    assert counts is None and np.array_equal(ids.cpu().numpy(), orc.route_topk(logits.numpy(), 4)[0])
+
+
+# ------------------------------------------------------------------ permute
+def random_ids(T, E, k, seed, skew=0.0):
+    rng = np.random.default_rng(seed)
+    logits = rng.normal(size=(T, E)) - skew * np.log(rng.permutation(E) + 1.0)
+    return orc.route_topk(logits.astype(np.float32), k)
+
+
+def groups_with_windows(counts, experts, rng):
+    groups = []
+    for e in experts:
+        n = int(counts[e])
+        style = int(rng.integers(0, 4))
+        if style == 0 or n < 4:
+            groups.append((int(e), 0, fe.ORD_MAX))
+        elif style == 1:                       # static head + replica tail
+            cut = int(rng.integers(1, n))
+            groups.append((int(e), 0, cut))
+            groups.append((int(e), cut, fe.ORD_MAX))
+        elif style == 2:                       # only a middle window is local
+            lo = int(rng.integers(0, n // 2))
+            groups.append((int(e), lo, lo + n // 3))
+        else:                                  # window entirely past the end -> empty group
+            groups.append((int(e), n + 5, n + 50))
+    order = rng.permutation(len(groups))
+    return [groups[i] for i in order]
+
+
+@pytest.mark.parametrize("T,E,k,d,skew,seed", [(512, 8, 2, 256, 0.0, 0), (3000, 128, 8, 64, 0.0, 1),
+                                               (2500, 128, 8, 520, 2.4, 2), (700, 40, 3, 8, 1.0, 3),
+                                               (5, 4, 2, 16, 0.0, 4), (9000, 1024, 4, 32, 1.5, 5)])
+def test_permute_parity(T, E, k, d, skew, seed):
+    say(f"permute T={T} E={E} k={k} d={d}")
+    rng = np.random.default_rng(100 + seed)
+    ids, _, counts = random_ids(T, E, k, seed, skew)
+    experts = rng.permutation(E)[: min(E, 40)]
+    groups = groups_with_windows(counts, experts, rng)
+    off_o, src_o, inv_o = orc.permute(ids, groups)
+    R = int(off_o[-1])
+    X = torch.randn((T, d), generator=torch.Generator().manual_seed(seed)).to(torch.bfloat16)
+    for R_cap in (R, R + 77):
+        Xp, off, src, inv = fe.feplb_permute(torch.from_numpy(ids).to(DEV), E, groups, X.to(DEV), R_cap)
+        torch.cuda.synchronize()
+        assert np.array_equal(off.cpu().numpy(), off_o)
+        assert np.array_equal(inv.cpu().numpy()[: T * k], inv_o)
+        assert np.array_equal(src.cpu().numpy()[:R], src_o)
+        want = X[torch.from_numpy(src_o.astype(np.int64) // k)]
+        assert torch.equal(Xp.cpu()[:R], want)            # byte copy: bit-exact
+
+
+def test_permute_degenerate_cases():
+    ids = torch.from_numpy(random_ids(64, 8, 2, 9)[0]).to(DEV)
+    X = torch.ones((64, 16), dtype=torch.bfloat16, device=DEV)
+    # no groups at all: nothing is local
+    Xp, off, src, inv = fe.feplb_permute(ids, 8, [], X, 4)
+    torch.cuda.synchronize()
+    assert off.cpu().tolist() == [0] and (inv.cpu().numpy()[:128] == -1).all()
+    # no tokens
+    Xp, off, src, inv = fe.feplb_permute(ids[:0], 8, [(1, 0, fe.ORD_MAX)], X[:0], 4)
+    torch.cuda.synchronize()
+    assert off.cpu().tolist() == [0, 0]
+    # capacity smaller than R: offsets and inv tell the truth, rows beyond R_cap are not written
+    groups = [(e, 0, fe.ORD_MAX) for e in range(8)]
+    off_o, src_o, inv_o = orc.permute(ids.cpu().numpy(), groups)
+    canary = torch.full((40,), -7, dtype=torch.int32, device=DEV)
+    Xp, off, src, inv = fe.feplb_permute(ids, 8, groups, X, 32, row_src=canary)
+    torch.cuda.synchronize()
+    assert np.array_equal(off.cpu().numpy(), off_o) and np.array_equal(inv.cpu().numpy()[:128], inv_o)
+    assert np.array_equal(canary.cpu().numpy()[:32], src_o[:32]) and (canary.cpu().numpy()[32:] == -7).all()
+    # index-only call (no X)
+    _, off2, src2, inv2 = fe.feplb_permute(ids, 8, groups, None, 128)
+    torch.cuda.synchronize()
+    assert np.array_equal(src2.cpu().numpy()[:128], src_o)
+
+
+# ------------------------------------------------------------------ expert FFN
+def make_weights(G, d, f, seed):
+    g = torch.Generator().manual_seed(seed)
+    out = []
+    for _ in range(G):
+        out.append(tuple((torch.randn(s, generator=g) * 0.05).to(torch.bfloat16) for s in ((d, f), (d, f), (f, d))))
+    return out
+
+
+@pytest.mark.parametrize("sizes,d,f", [([128, 0, 1, 129, 300, 0, 64, 255], 256, 128),
+                                       ([5, 700], 512, 384), ([0, 0, 0], 256, 128), ([1], 768, 256)])
+@pytest.mark.parametrize("yp_dtype", [torch.float32, torch.bfloat16])
+def test_grouped_ffn_parity(sizes, d, f, yp_dtype):
+    say(f"ffn sizes={sizes} d={d} f={f} {yp_dtype}")
+    G = len(sizes)
+    offsets = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    R = int(offsets[-1])
+    R_cap = R + 37
+    Xp = torch.randn((R_cap, d), generator=torch.Generator().manual_seed(7)).to(torch.bfloat16)
+    W = make_weights(G, d, f, 11)
+    Wd = [tuple(m.to(DEV) for m in w) for w in W]
+    H = torch.full((R_cap, f), 512.0, dtype=torch.bfloat16, device=DEV)
+    Yp = torch.full((R_cap, d), 512.0, dtype=yp_dtype, device=DEV)
+    fe.feplb_grouped_ffn(Xp.to(DEV), torch.from_numpy(offsets).to(DEV), 0, G, d, f,
+                         [w[0] for w in Wd], [w[1] for w in Wd], [w[2] for w in Wd], H, Yp)
+    torch.cuda.synchronize()
+    H_o, Yp_o = orc.grouped_ffn(f64(Xp)[:R], offsets, [tuple(f64(m) for m in w) for w in W])
+    if R:
+        eh = bf16_rounding_excess(f64(H)[:R], H_o)
+        ey = row_rel_err(f64(Yp)[:R], Yp_o)
+        say(f"  H rounding excess {eh:.3f} (<= 1)  Yp err {ey.max():.5f}")
+        assert eh <= 1.0 and ey.max() <= ROW_TOL
+    # rows past R are never touched
+    assert (H[R:].float() == 512.0).all() and (Yp[R:].float() == 512.0).all()
+
+
+def test_grouped_ffn_range_split_equals_one_call():
+    # static range then dynamic range (two launches) gives the same bytes as one launch
+    sizes = [200, 3, 0, 150, 90]
+    d, f, G = 256, 256, 5
+    offsets = torch.tensor(np.concatenate([[0], np.cumsum(sizes)]), dtype=torch.int32, device=DEV)
+    R = int(sum(sizes))
+    Xp = torch.randn((R, d), generator=torch.Generator().manual_seed(3)).to(torch.bfloat16).to(DEV)
+    W = [tuple(m.to(DEV) for m in w) for w in make_weights(G, d, f, 5)]
+    cols = [[w[i] for w in W] for i in range(3)]
+    H1 = torch.zeros((R, f), dtype=torch.bfloat16, device=DEV); Y1 = torch.zeros((R, d), device=DEV)
+    H2 = torch.zeros_like(H1); Y2 = torch.zeros_like(Y1)
+    fe.feplb_grouped_ffn(Xp, offsets, 0, G, d, f, *cols, H1, Y1)
+    fe.feplb_grouped_ffn(Xp, offsets, 0, 3, d, f, *cols, H2, Y2)
+    fe.feplb_grouped_ffn(Xp, offsets, 3, G, d, f, *cols, H2, Y2)
+    torch.cuda.synchronize()
+    assert torch.equal(H1, H2) and torch.equal(Y1, Y2)
+
+
+# ------------------------------------------------------------------ combine
+@pytest.mark.parametrize("T,k,d,yp_dtype", [(100, 2, 256, torch.float32), (333, 8, 520, torch.float32),
+                                            (64, 8, 1024, torch.bfloat16), (7, 1, 8, torch.float32)])
+def test_combine_parity(T, k, d, yp_dtype):
+    say(f"combine T={T} k={k} d={d} {yp_dtype}")
+    rng = np.random.default_rng(T + k)
+    R = (T * k) // 2
+    slots = rng.permutation(T * k)[:R]
+    inv = np.full(T * k, -1, dtype=np.int32)
+    inv[slots] = np.arange(R, dtype=np.int32)
+    for t in range(0, T, 9):
+        inv[t * k:(t + 1) * k] = -1            # tokens without any local slot
+    Yp = torch.randn((R, d), generator=torch.Generator().manual_seed(2)).to(yp_dtype)
+    w = torch.rand((T, k), generator=torch.Generator().manual_seed(3))
+    Y = fe.feplb_unpermute_combine(Yp.to(DEV), torch.from_numpy(inv).to(DEV), w.to(DEV), T, k, d)
+    torch.cuda.synchronize()
+    want = orc.combine(f64(Yp), inv, f64(w), T, k)
+    got = f64(Y)
+    # one bf16 rounding of an fp32 sum: half an ulp of the result plus fp32 noise
+    assert np.all(np.abs(got - want) <= 2.0**-8 * np.abs(want) + 1e-6)
+    assert row_rel_err(got, want).max() <= ROW_TOL
+    for t in range(0, T, 9):
+        assert np.all(Y[t].cpu().view(torch.int16).numpy() == 0)       # +0, all bits clear
+
+
+# ------------------------------------------------------------------ whole layer, reduced sizes
+def oracle_layer(p, Y):
+    """Runs the oracle on the prepared workload and compares every output of the
+    HIP layer element by element. Returns the largest float error."""
+    wl, b = p.wl, p.layer.buf
+    ids, w, counts = orc.route_topk(wl.logits.cpu().numpy(), wl.k)
+    assert np.array_equal(b.topk_ids.cpu().numpy(), ids), "top-k ids"
+    assert np.array_equal(b.counts.cpu().numpy(), counts), "counts"
+    assert np.abs(b.topk_w.cpu().numpy() - w).max() <= 1e-6, "top-k weights"
+    if p.rebalanced:
+        this = orc.pick_receiver(wl.P, wl.owner(), counts)
+        assert this == p.rank, "receiving rank"
+        moves, before, after = orc.plan_overflow(wl.P, wl.owner(), counts, wl.dyn_flags(4), p.slots, this)
+        assert [tuple(m) for m in p.moves] == [tuple(m) for m in moves], "plan"
+        groups = [(int(e), 0, orc.INT32_MAX) for e in wl.local_experts(this)]
+        groups += [(m[0], m[4], m[4] + m[3]) for m in moves]
+        assert groups == [tuple(g) for g in p.groups]
+    else:
+        groups = [(int(e), 0, orc.INT32_MAX) for e in wl.local_experts()]
+    G = len(groups)
+    offsets, row_src, inv = orc.permute(ids, groups)
+    R = int(offsets[-1])
+    assert R == p.R
+    assert np.array_equal(b.offsets.cpu().numpy()[: G + 1], offsets), "offsets"
+    assert np.array_equal(b.inv.cpu().numpy()[: wl.T * wl.k], inv), "inv"
+    assert np.array_equal(b.row_src.cpu().numpy()[:R], row_src), "row_src"
+    X64 = f64(wl.X)
+    assert torch.equal(b.Xp.cpu()[:R], wl.X.cpu()[torch.from_numpy(row_src.astype(np.int64) // wl.k)]), "Xp"
+    W = [tuple(f64(m) for m in wl.expert_weights(g[0])) for g in groups]
+    H_o, Yp_o = orc.grouped_ffn(orc.gather_rows(X64, row_src, wl.k), offsets, W)
+    want = orc.combine(Yp_o, inv, w, wl.T, wl.k)
+    eh = bf16_rounding_excess(f64(b.H)[:R], H_o) if R else 0.0
+    ey = row_rel_err(f64(b.Yp)[:R], Yp_o).max() if R else 0.0
+    e = row_rel_err(f64(Y), want)
+    glob = np.abs(f64(Y) - want).max() / np.sqrt((want ** 2).mean())
+    say(f"  {wl.name}: R={R} groups={np.diff(offsets).tolist()} H excess {eh:.3f} Yp {ey:.4f} "
+        f"Y per-row {e.max():.4f} (bound {ROW_TOL}); max-abs/global-RMS {glob:.4f}")
+    assert eh <= 1.0 and ey <= ROW_TOL and e.max() <= ROW_TOL
+    # tokens with no local slot are exactly +0
+    none = np.nonzero((inv.reshape(wl.T, wl.k) < 0).all(axis=1))[0]
+    assert np.all(Y.cpu().view(torch.int16).numpy()[none] == 0)
+    return e.max()
+
+
+REDUCED = {
+    "C1": {},                                                     # the tiny workload at its full size
+    "C2": dict(T=1536, d=512, f=384),                             # ~1.5k rows over 16 groups of ~96: ragged tails
+    "C3": dict(T=2048, d=512, f=256),                             # hot groups of ~2k rows: many tiles + empty groups
+    "C5": dict(T=2048, d=768, f=256),                             # 32 groups, several empty
+}
+
+
+@pytest.mark.parametrize("name", list(REDUCED))
+def test_layer_parity_reduced(name):
+    say(f"layer {name} reduced {REDUCED[name]}")
+    p = runner.prepare(name, DEV, **REDUCED[name])
+    Y = runner.step(p)
+    torch.cuda.synchronize()
+    oracle_layer(p, Y)
+
+
+@pytest.mark.parametrize("source_kind", ["device", "pinned"])
+def test_rebalanced_layer_parity_reduced(source_kind):
+    say(f"layer C4 reduced, replicas staged from {source_kind} memory")
+    p = runner.prepare("C4", DEV, T=8 * 512, d=512, f=256, source_kind=source_kind)
+    Y = runner.step(p)
+    torch.cuda.synchronize()
+    assert len(p.moves) == 4 and sum(m[3] for m in p.moves) > 0
+    oracle_layer(p, Y)
+    # the side-stream copy and the same copy issued in stream order give the same bytes
+    Y1 = Y.clone()
+    Y2 = runner.step(p, overlap=False)
+    torch.cuda.synchronize()
+    assert torch.equal(Y1, Y2)
+
+
+def test_output_does_not_depend_on_where_an_experts_rows_run():
+    # Section 2.2: each token is still processed by the same expert with identical weights, so
+    # splitting an expert's batch between its owner's group and a replica's group (a copy of the
+    # weights) must not change any token's result.  Bit-identical here, because a row's arithmetic
+    # does not depend on which tile it sits in.
+    p = runner.prepare("C3", DEV, T=2048, d=512, f=256)
+    Y_whole = runner.step(p).clone()
+    torch.cuda.synchronize()
+    hot = int(np.argmax(p.counts[[g[0] for g in p.groups]]))
+    e, n = p.groups[hot][0], int(p.counts[p.groups[hot][0]])
+    assert n > 300
+    cut = n - n // 3
+    split = list(p.groups)
+    split[hot] = (e, 0, cut)
+    split.append((e, cut, cut + n // 3))                      # replica takes the tail
+    replica = tuple(m.clone() for m in p.weights[hot])
+    layer = fe.RankLayer(p.wl.T, p.wl.E, p.wl.k, p.wl.d, p.wl.f, R_cap=p.R, G_cap=len(split), device=DEV)
+    Y_split = layer.forward(p.wl.logits, p.wl.X, split, list(p.weights) + [replica])
+    torch.cuda.synchronize()
+    assert int(layer.buf.offsets[len(split)].item()) == p.R
+    assert torch.equal(Y_whole, Y_split)
+
+
+def test_layer_is_deterministic():
+    p = runner.prepare("C3", DEV, T=2048, d=512, f=256)
+    Y1 = runner.step(p).clone()
+    ids1 = p.layer.buf.topk_ids.clone(); inv1 = p.layer.buf.inv.clone()
+    Y2 = runner.step(p)
+    torch.cuda.synchronize()
+    assert torch.equal(Y1, Y2) and torch.equal(ids1, p.layer.buf.topk_ids) and torch.equal(inv1, p.layer.buf.inv)
+
+
+# ------------------------------------------------------------------ full sizes, as benchmarked
+def sampled_check(p, Y, stride):
+    """Integer outputs in full; float output on a sample of tokens (every
+    `stride`-th token plus the first and last row of every group) that the
+    oracle computes one by one from the layer's definition."""
+    wl, b = p.wl, p.layer.buf
+    ids, w, counts = orc.route_topk(wl.logits.cpu().numpy(), wl.k)
+    assert np.array_equal(b.topk_ids.cpu().numpy(), ids), "top-k ids"
+    assert np.array_equal(b.counts.cpu().numpy(), counts), "counts"
+    assert np.abs(b.topk_w.cpu().numpy() - w).max() <= 1e-6, "top-k weights"
+    if p.rebalanced:
+        this = orc.pick_receiver(wl.P, wl.owner(), counts)
+        moves, _, after = orc.plan_overflow(wl.P, wl.owner(), counts, wl.dyn_flags(4), p.slots, this)
+        assert this == p.rank and [tuple(m) for m in p.moves] == [tuple(m) for m in moves]
+        groups = [(int(e), 0, orc.INT32_MAX) for e in wl.local_experts(this)] + [(m[0], m[4], m[4] + m[3]) for m in moves]
+    else:
+        groups = [(int(e), 0, orc.INT32_MAX) for e in wl.local_experts()]
+    G = len(groups)
+    offsets, row_src, inv = orc.permute(ids, groups)
+    R = int(offsets[-1])
+    assert np.array_equal(b.offsets.cpu().numpy()[: G + 1], offsets), "offsets"
+    assert np.array_equal(b.inv.cpu().numpy()[: wl.T * wl.k], inv), "inv"
+    assert np.array_equal(b.row_src.cpu().numpy()[:R], row_src), "row_src"
+    # Xp rows are byte copies: check a strided sample of rows against X
+    rows = np.unique(np.concatenate([np.arange(0, R, 97), offsets[:-1][np.diff(offsets) > 0], offsets[1:][np.diff(offsets) > 0] - 1]))
+    src_tok = torch.from_numpy(row_src[rows].astype(np.int64) // wl.k).to(DEV)
+    assert torch.equal(b.Xp[torch.from_numpy(rows).to(DEV)], wl.X[src_tok]), "Xp"
+    edge_rows = np.concatenate([offsets[:-1][np.diff(offsets) > 0], offsets[1:][np.diff(offsets) > 0] - 1])
+    toks = np.unique(np.concatenate([np.arange(0, wl.T, stride), row_src[edge_rows] // wl.k, [wl.T - 1]]))
+    keep = inv.reshape(wl.T, wl.k)[toks] >= 0
+    want = orc.moe_tokens(f64(wl.X[torch.from_numpy(toks).to(DEV)]), ids[toks], w[toks], keep,
+                          lambda e: tuple(f64(m) for m in wl.expert_weights(e)))
+    got = f64(Y[torch.from_numpy(toks).to(DEV)])
+    e = row_rel_err(got, want)
+    say(f"  {wl.name} full size: T={wl.T} R={R} groups={np.diff(offsets).tolist()} sampled tokens={len(toks)} "
+        f"per-row err max {e.max():.4f} (bound {ROW_TOL})")
+    assert e.max() <= ROW_TOL
+    return e.max()
+
+
+@pytest.mark.parametrize("name,stride", [("C2", 16), ("C3", 16), ("C4", 256), ("C5", 64)])
+def test_layer_parity_full_size_sampled(name, stride):
+    say(f"layer {name} at full size")
+    p = runner.prepare(name, DEV)
+    Y = runner.step(p)
+    torch.cuda.synchronize()
+    sampled_check(p, Y, stride)
+    p.wl.drop_weights()
+    torch.cuda.empty_cache()
+
+
+# ------------------------------------------------------------------ error paths that need a device pointer
+def test_misaligned_and_small_workspace_are_refused():
+    ids = torch.zeros((16, 2), dtype=torch.int32, device=DEV)
+    X = torch.zeros((16, 64), dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(fe.FeplbError, match="workspace"):
+        fe.feplb_permute(ids, 4, [(0, 0, fe.ORD_MAX)], X, 32, ws=torch.empty((16,), dtype=torch.uint8, device=DEV))
+    Xbad = torch.zeros((16 * 64 + 4,), dtype=torch.bfloat16, device=DEV)[4:].view(16, 64)
+    with pytest.raises(fe.FeplbError, match="aligned"):
+        fe.feplb_permute(ids, 4, [(0, 0, fe.ORD_MAX)], Xbad, 32)
+    with pytest.raises(fe.FeplbError, match="d %"):
+        H = torch.zeros((8, 128), dtype=torch.bfloat16, device=DEV)
+        fe.feplb_grouped_ffn(X[:8], torch.zeros(2, dtype=torch.int32, device=DEV), 0, 1, 64, 128,
+                             [X], [X], [X], H, torch.zeros((8, 64), device=DEV))

@@ -1,0 +1,116 @@
+"""Host-side checks that need no GPU: the library loads, exports every symbol
+the header declares, validates arguments before touching the device, and its
+host-only plan is bit-identical to the oracle's."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2604_19654_amd as fe
+from oracle import feplb_oracle as orc
+from tests.test_oracle_pins import read_golden, random_plan_case
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "feplb.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(feplb_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    L = fe.lib()
+    names = declared_functions()
+    assert {"feplb_route_topk", "feplb_permute", "feplb_grouped_ffn", "feplb_unpermute_combine",
+            "feplb_plan", "feplb_stage_weights"} <= set(names)
+    for name in names:
+        assert hasattr(L, name), f"{name} is declared in feplb.h but not exported"
+    assert "gfx950" in fe.version()
+
+
+def test_expert_bytes_matches_the_papers_expert_size():
+    assert fe.feplb_expert_bytes(6144, 2048) == 72 * 2**20          # Section 2.3: 72 MiB per expert
+    assert 8 * fe.feplb_expert_bytes(6144, 2048) == 576 * 2**20     # 8 slots = 576 MiB
+
+
+def test_argument_validation_happens_before_any_device_work():
+    L = fe.lib()
+    assert L.feplb_route_topk(None, 4, 4, 5, None, None, None, None) == -2       # k > E
+    assert L.feplb_route_topk(None, 4, 4000, 2, None, None, None, None) == -2    # E above the limit
+    assert L.feplb_route_topk(None, -1, 4, 2, None, None, None, None) == -1
+    assert b"route_topk" in L.feplb_last_error()
+    assert L.feplb_unpermute_combine(None, 0, None, None, 4, 2, 12, None, None) == -2   # d % 8
+    assert L.feplb_unpermute_combine(None, 7, None, None, 4, 2, 16, None, None) == -1   # dtype
+    g = (fe.Group * 2)(fe.Group(0, 0, 10), fe.Group(0, 5, 20))
+    rc = L.feplb_permute(None, 0, 2, 4, g, 2, None, 0, None, 0, 16, None, None, None, 0, None)
+    assert rc == -1 and b"overlap" in L.feplb_last_error()
+    rc = L.feplb_grouped_ffn(None, None, 0, 1, 128, 100, 128, None, None, None, None, None, 0, 7, None, 0, None)
+    assert rc == -2
+    rc = L.feplb_grouped_ffn(None, None, 0, 1, 128, 256, 128, None, None, None, None, None, 0, 0, None, 0, None)
+    assert rc == -1
+    assert fe.feplb_permute_workspace_bytes(1024, 8, 128, 20) > 0
+    assert fe.feplb_grouped_ffn_workspace_bytes(4096, 20) >= (4096 // 128 + 20) * 16
+
+
+def as_tuples(moves):
+    return [tuple(int(v) for v in m) for m in moves]
+
+
+@pytest.mark.parametrize("name", ["plan_whole_example.txt", "plan_whole_tau_example.txt"])
+def test_plan_whole_golden(name):
+    g = read_golden(name)
+    moves, before, after, _ = fe.feplb_plan(g["P"][0], g["owner"], g["n"], g["dyn_flag"], g["slots"],
+                                            g["tau"][0], fe.PLAN_WHOLE)
+    assert [m[:4] for m in moves] == g["moves"]
+    assert before.tolist() == g["load_before"] and after.tolist() == g["load_after"]
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_plan_matches_oracle_bit_for_bit(seed):
+    rng = np.random.default_rng(1000 + seed)
+    P, per = int(rng.integers(1, 9)), int(rng.integers(1, 33))
+    E, owner, n, dyn, slots, tau = random_plan_case(rng, P, per)
+    m_o, b_o, a_o = orc.plan_whole(P, owner, n, dyn, slots, tau)
+    m_l, b_l, a_l, _ = fe.feplb_plan(P, owner, n, dyn, slots, tau, fe.PLAN_WHOLE)
+    assert as_tuples(m_l) == as_tuples(m_o)
+    assert np.array_equal(b_l, b_o) and np.array_equal(a_l, a_o)
+    if P > 1:
+        this = orc.pick_receiver(P, owner, n)
+        m_o, b_o, a_o = orc.plan_overflow(P, owner, n, dyn, slots, this)
+        m_l, b_l, a_l, chosen = fe.feplb_plan(P, owner, n, dyn, slots, 0, fe.PLAN_OVERFLOW, -1)
+        assert chosen == this
+        assert as_tuples(m_l) == as_tuples(m_o)
+        assert np.array_equal(b_l, b_o) and np.array_equal(a_l, a_o)
+        fixed = int(rng.integers(0, P))
+        m_o, _, a_o = orc.plan_overflow(P, owner, n, dyn, slots, fixed)
+        m_l, _, a_l, chosen = fe.feplb_plan(P, owner, n, dyn, slots, 0, fe.PLAN_OVERFLOW, fixed)
+        assert chosen == fixed and as_tuples(m_l) == as_tuples(m_o) and np.array_equal(a_l, a_o)
+
+
+def test_plan_is_the_same_on_every_rank_and_on_the_full_size_counts():
+    # 128 experts, EP = 8, four dynamic experts per rank, eight slots (Section 2.3 numbers)
+    import workloads
+    wl = workloads.make("C4", T=4096, d=8, f=8)
+    _, _, counts = orc.route_topk(wl.logits.numpy(), wl.k)
+    args = (8, wl.owner(), counts, wl.dyn_flags(4), [8] * 8, 64)
+    first = fe.feplb_plan(*args, fe.PLAN_WHOLE)
+    for _ in range(8):                                  # every rank derives the same plan
+        again = fe.feplb_plan(*args, fe.PLAN_WHOLE)
+        assert again[0] == first[0] and np.array_equal(again[2], first[2])
+    assert as_tuples(first[0]) == as_tuples(orc.plan_whole(*args)[0])
+    assert orc.token_straggler(first[2]) < orc.token_straggler(first[1])
+
+
+def test_plan_error_codes():
+    L = fe.lib()
+    with pytest.raises(fe.FeplbError):
+        fe.feplb_plan(2, [0, 5], [1, 1], [1, 1], [1, 1])            # owner out of range
+    with pytest.raises(fe.FeplbError):
+        fe.feplb_plan(2, [0, 1], [1, -1], [1, 1], [1, 1])           # negative count
+    with pytest.raises(fe.FeplbError):
+        fe.feplb_plan(2, [0, 0, 1], [9, 5, 0], [1, 1, 1], [4, 4], 1, fe.PLAN_WHOLE, -1, max_moves=0)
+    with pytest.raises(fe.FeplbError):
+        fe.feplb_plan(2, [0, 1], [1, 1], [1, 1], [1, 1], 0, 9)      # unknown mode

@@ -388,6 +388,16 @@ def test_layer_partial_locality_and_missing_tokens():
     assert seen_empty
 
 
+def test_batched_per_token_definition_matches_the_single_token_one():
+    logits, X, W = small_layer(7, T=30, E=16, k=4)
+    ids, w, _ = orc.route_topk(logits, 4)
+    local = [1, 2, 8, 15]
+    got = orc.moe_tokens(X, ids, w, np.isin(ids, local), lambda e: W[e])
+    Wl = {e: W[e] for e in local}
+    for t in range(30):
+        assert np.allclose(got[t], orc.moe_token(X[t], ids[t], w[t], Wl), atol=1e-12)
+
+
 def test_identical_experts_make_the_layer_a_plain_mlp():
     # with every expert equal, sum_j w_j FFN(x) = FFN(x) because the weights sum to one
     logits, X, W = small_layer(3)

@@ -29,3 +29,16 @@ def row_rel_err(got: np.ndarray, want: np.ndarray) -> np.ndarray:
     out[nz] = err[nz] / rms[nz]
     out[~nz] = np.where(err[~nz] == 0, 0.0, np.inf)
     return out
+
+
+def bf16_rounding_excess(got: np.ndarray, want: np.ndarray) -> float:
+    """For an INTERMEDIATE kept in bf16 (the SwiGLU activations H): every element
+    must sit within one bf16 rounding step of the oracle value, plus a small
+    allowance (1e-3 of the row RMS) for fp32 accumulation order and the fast
+    exponential.  H rows are heavy-tailed (a product of two near-Gaussians), so
+    their largest element's rounding step alone can exceed 2e-2 of the row RMS;
+    the 2e-2 bar applies to the layer's outputs, not to this intermediate.
+    Returns max over elements of |err| / allowed (<= 1 passes)."""
+    rms = np.sqrt((want ** 2).mean(axis=1, keepdims=True))
+    allowed = 2.0 ** -8 * np.abs(want) + 1e-3 * rms + 1e-30
+    return float((np.abs(got - want) / allowed).max())
