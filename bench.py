@@ -1,0 +1,252 @@
+#!/usr/bin/env python3
+"""Benchmark of one EP rank's MoE hot path on one MI355X.
+
+A step is one pass of the whole path (route -> [plan + staging] -> permute ->
+grouped SwiGLU FFN -> combine) over one synthetic batch that is already
+resident in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4] [--no-cpu-baseline] [--all]
+
+value      = FFN flops of the step (6*d*f per permuted row) / wall time of the WHOLE step
+roofline   = the gate/up GEMM (the dominant kernel): 4*d*f flops per row over its
+             average launch duration, measured with HIP events on the launch stream
+cpu_baseline = the CPU oracle timed on a bounded sample of the same workload
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 (no sparsity)
+HBM_PEAK_GBPS = 8000.0
+METRIC = "grouped-FFN TFLOP/s & % bf16 MFMA peak per rank share; permute/combine GB/s"
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def time_workload(name, steps, warmup, source_kind="device"):
+    import numpy as np
+    import torch
+    from paper_2604_19654_amd import runner
+
+    p = runner.prepare(name, "cuda:0", source_kind=source_kind)
+    wl, layer = p.wl, p.layer
+    for _ in range(warmup):
+        runner.step(p, mark=True)
+    torch.cuda.synchronize()
+    tl = layer.timeline
+    acc = {}
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        runner.step(p, mark=True)
+        # the step's events are complete once the stream drains; reading them costs one sync per
+        # step, which a rebalanced step already pays for its counts read-back
+        tl["combined"].synchronize()
+
+        def span(a, b, key):
+            if a in tl and b in tl:
+                acc[key] = acc.get(key, 0.0) + tl[a].elapsed_ms(tl[b])
+        span("start", "routed", "route")
+        span("start", "combined", "step_events")
+        if p.rebalanced:
+            span("static_scheduled", "static_gate_up", "gate_up")
+            span("static_gate_up", "static_down", "down")
+            span("dynamic_scheduled", "dynamic_gate_up", "gate_up")
+            span("dynamic_gate_up", "dynamic_down", "down")
+            span("copy_start", "permuted", "_ignore")
+            acc["copy"] = acc.get("copy", 0.0) + _copy_ms(layer)
+            span("static_down", "staged", "wait_for_copy")
+            span("dynamic_done", "combined", "combine")
+            span("routed", "permuted", "plan_stage_permute")
+        else:
+            span("routed", "permuted", "permute")
+            span("static_scheduled", "static_gate_up", "gate_up")
+            span("static_gate_up", "static_down", "down")
+            span("static_down", "combined", "combine")
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    ms = {k: v / steps for k, v in acc.items() if not k.startswith("_")}
+    n_up = 2 if (p.rebalanced and len(p.groups) > len(p.static_weights)) else 1
+    R, d, f, T, k = p.R, wl.d, wl.f, wl.T, wl.k
+    ffn_flops = 6.0 * d * f * R
+    yp_bytes = layer.buf.Yp.element_size()
+    res = dict(
+        workload=name, T=T, R=R, d=d, f=f, E=wl.E, k=k, groups=len(p.groups), rank=p.rank,
+        ms_per_step=wall_ms, ms=ms,
+        ffn_tflops_step=ffn_flops / (wall_ms * 1e-3) / 1e12,
+        ffn_tflops_kernels=ffn_flops / ((ms["gate_up"] + ms["down"]) * 1e-3) / 1e12,
+        gate_up_tflops=4.0 * d * f * R / (ms["gate_up"] * 1e-3) / 1e12,
+        down_tflops=2.0 * d * f * R / (ms["down"] * 1e-3) / 1e12,
+        gate_up_launches_per_step=n_up,
+        gate_up_ms_per_launch=ms["gate_up"] / n_up,
+        combine_gbps=(R * d * yp_bytes + T * d * 2 + T * k * 8) / (ms["combine"] * 1e-3) / 1e9,
+        route_gbps=(T * wl.E * 4 + T * k * 8) / (ms["route"] * 1e-3) / 1e9,
+    )
+    if "permute" in ms:
+        res["permute_gbps"] = (2 * R * d * 2 + T * k * 8 + R * 4) / (ms["permute"] * 1e-3) / 1e9
+    if p.rebalanced:
+        nbytes = sum(t.numel() * t.element_size() for t in p.remote_sources.values())
+        res["staging"] = dict(bytes=nbytes, source=p.source_kind, copy_ms=ms["copy"],
+                              copy_gbps=nbytes / (ms["copy"] * 1e-3) / 1e9,
+                              wait_after_static_ms=ms["wait_for_copy"])
+        res["moves"] = p.moves
+    res["pct_mfma_peak_ffn_kernels"] = 100.0 * res["ffn_tflops_kernels"] / MFMA_BF16_PEAK_TFLOPS
+    return p, res
+
+
+def _copy_ms(layer):
+    tl = layer.timeline
+    if "copy_start" not in tl:
+        return 0.0
+    start, end = tl["copy_start"], layer.staged
+    end.synchronize()
+    return start.elapsed_ms(end)
+
+
+def cpu_baseline(p, budget_tokens):
+    """The oracle as it stands, on a bounded sample: full routing, plan and
+    permutation (integer work), then the layer's per-token definition on a
+    strided sample of tokens; the FFN flops of the sampled local rows over the
+    time of that last part give the oracle's TFLOP/s."""
+    import numpy as np
+    import torch
+    from oracle import feplb_oracle as orc
+    from tests.util import f64, row_rel_err
+
+    wl = p.wl
+    t0 = time.perf_counter()
+    ids, w, counts = orc.route_topk(wl.logits.cpu().numpy(), wl.k)
+    if p.rebalanced:
+        this = orc.pick_receiver(wl.P, wl.owner(), counts)
+        moves, _, _ = orc.plan_overflow(wl.P, wl.owner(), counts, wl.dyn_flags(4), p.slots, this)
+        groups = [(int(e), 0, orc.INT32_MAX) for e in wl.local_experts(this)] + \
+                 [(m[0], m[4], m[4] + m[3]) for m in moves]
+    else:
+        groups = [(int(e), 0, orc.INT32_MAX) for e in wl.local_experts()]
+    offsets, row_src, inv = orc.permute(ids, groups)
+    t_int = time.perf_counter() - t0
+    stride = max(1, wl.T // budget_tokens)
+    toks = np.arange(0, wl.T, stride)
+    keep = inv.reshape(wl.T, wl.k)[toks] >= 0
+    rows = int(keep.sum())
+    tt = torch.from_numpy(toks).to(wl.X.device)
+    x = f64(wl.X[tt])
+    t1 = time.perf_counter()
+    want = orc.moe_tokens(x, ids[toks], w[toks], keep, lambda e: tuple(f64(m) for m in wl.expert_weights(e)))
+    t_ffn = time.perf_counter() - t1
+    got = f64(p.layer.buf.Y[tt])
+    err = float(row_rel_err(got, want).max())
+    ints_ok = bool(np.array_equal(p.layer.buf.topk_ids.cpu().numpy(), ids)
+                   and np.array_equal(p.layer.buf.inv.cpu().numpy()[: wl.T * wl.k], inv)
+                   and np.array_equal(p.layer.buf.offsets.cpu().numpy()[: len(groups) + 1], offsets))
+    cores = torch.get_num_threads()
+    return dict(value=6.0 * wl.d * wl.f * rows / t_ffn / 1e12, unit="TFLOP/s", cores=cores, kind="oracle",
+                sample=f"{wl.name}: every {stride}th token ({len(toks)} tokens, {rows} local rows) through the "
+                       f"fp64 per-token definition incl. widening {len(set(g[0] for g in groups))} experts' "
+                       f"weights: {t_ffn:.1f} s; full routing+plan+permutation oracle (integer outputs): {t_int:.1f} s",
+                seconds=t_ffn, integer_seconds=t_int, sample_max_row_err=err, integer_outputs_match=ints_ok)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="C4")
+    ap.add_argument("--source", default="device", choices=["device", "pinned"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--all", action="store_true", help="also time the other four workloads (reported under all_workloads)")
+    ap.add_argument("--cpu-tokens", type=int, default=512)
+    a = ap.parse_args()
+    if a.gpus != 1:
+        log("bench.py: this build is a single-GPU hot path (one EP rank's share); run it with --gpus 1")
+        sys.exit(2)
+    import torch
+    import paper_2604_19654_amd as fe
+    if not torch.cuda.is_available():
+        log("bench.py needs a GPU")
+        sys.exit(2)
+    fe.lib()  # fail loudly if the HIP library is missing
+    prop = torch.cuda.get_device_properties(0)
+    p, res = time_workload(a.workload, a.steps, a.warmup, a.source)
+    log(json.dumps(res))
+    cpu = None
+    if not a.no_cpu_baseline:
+        cpu = cpu_baseline(p, a.cpu_tokens)
+    others = {}
+    if a.all:
+        p.wl.drop_weights()
+        del p
+        torch.cuda.empty_cache()
+        for name in ("C1", "C2", "C3", "C5", "C4"):
+            if name == a.workload:
+                continue
+            q, r = time_workload(name, a.steps, a.warmup, a.source)
+            log(json.dumps(r))
+            others[name] = {k: r[k] for k in ("R", "ms_per_step", "ffn_tflops_kernels", "pct_mfma_peak_ffn_kernels",
+                                              "gate_up_tflops", "down_tflops", "combine_gbps", "route_gbps")
+                            } | ({"permute_gbps": r["permute_gbps"]} if "permute_gbps" in r else {})
+            q.wl.drop_weights()
+            del q
+            torch.cuda.empty_cache()
+    up_tflops = res["gate_up_tflops"]
+    out = {
+        "metric": METRIC, "value": res["ffn_tflops_step"], "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": a.steps, "warmup": a.warmup, "ms_per_step": res["ms_per_step"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{a.workload} ({_describe(a.workload)})", "T": res["T"], "R": res["R"],
+                   "d": res["d"], "f": res["f"], "E": res["E"], "k": res["k"], "groups": res["groups"],
+                   "yp_dtype": "f32", "staging_source": a.source if a.workload == "C4" else None},
+        "roofline": {"kernel": "grouped_gemm_kernel<0,true> (gate/up GEMM + SwiGLU)", "bound": "mfma",
+                     "achieved": up_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": up_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "launches_per_step": res["gate_up_launches_per_step"],
+                     "avg_launch_ms": res["gate_up_ms_per_launch"],
+                     "flops_per_launch": 4.0 * res["d"] * res["f"] * res["R"] / res["gate_up_launches_per_step"]},
+        "cpu_baseline": cpu,
+        "detail": {k: res[k] for k in res if k not in ("workload",)},
+        "device": _device_info(prop),
+    }
+    if others:
+        out["all_workloads"] = others
+    print(json.dumps(out), flush=True)
+
+
+def _device_info(prop):
+    """CU count and clock as the runtime reports them, and the bf16 MFMA peak they imply
+    (CUs x 4 SIMDs x 1024 flop/clk x clock); the published 2.5 PFLOP/s is what fractions use."""
+    khz = getattr(prop, "clock_rate", None)
+    if khz is None:
+        try:
+            import ctypes
+            from paper_2604_19654_amd.binding import hip_runtime
+            v = ctypes.c_int(0)
+            # hipDeviceAttributeClockRate: peak clock in kHz
+            hip = hip_runtime()
+            hip.hipDeviceGetAttribute.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.c_int, ctypes.c_int]
+            if hip.hipDeviceGetAttribute(ctypes.byref(v), 5, 0) == 0 and v.value > 0:
+                khz = v.value
+        except Exception:
+            khz = None
+    info = {"name": prop.name, "cus": prop.multi_processor_count, "hbm_gb": prop.total_memory / 2**30}
+    if khz:
+        info["clock_mhz"] = khz / 1e3
+        info["derived_bf16_peak_tflops"] = prop.multi_processor_count * 4 * 1024 * khz * 1e3 / 1e12
+    return info
+
+
+def _describe(name):
+    return {"C1": "tiny, 8 experts all local", "C2": "balanced rank share, EP=8",
+            "C3": "skewed straggler share, EP=8", "C4": "FEPLB-rebalanced share: 16 static + 4 replicated experts",
+            "C5": "large share, EP=4"}[name]
+
+
+if __name__ == "__main__":
+    main()

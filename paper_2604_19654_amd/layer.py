@@ -79,6 +79,22 @@ class RankLayer:
         s = self.buf.slots[i]
         return s[: d * f].view(d, f), s[d * f: 2 * d * f].view(d, f), s[2 * d * f:].view(f, d)
 
+    def _ffn_range(self, g0, g1, wg, wu, wd, tag, mark):
+        """One ragged launch per GEMM for groups [g0, g1).  With mark=True the
+        schedule / gate_up / down launches are issued by separate calls so that
+        HIP events can bracket each GEMM kernel on its stream."""
+        b = self.buf
+        args = (b.Xp, b.offsets, g0, g1, self.d, self.f, wg, wu, wd, b.H, b.Yp)
+        if not mark:
+            B.feplb_grouped_ffn(*args, phases=B.FFN_ALL, ws=b.ws_ffn)
+            return
+        B.feplb_grouped_ffn(*args, phases=B.FFN_SCHEDULE, ws=b.ws_ffn)
+        self._mark(tag + "_scheduled", True)
+        B.feplb_grouped_ffn(*args, phases=B.FFN_GATE_UP, ws=b.ws_ffn)
+        self._mark(tag + "_gate_up", True)
+        B.feplb_grouped_ffn(*args, phases=B.FFN_DOWN, ws=b.ws_ffn)
+        self._mark(tag + "_down", True)
+
     # -- static-only layer (no dynamic experts) ---------------------------
     def forward(self, logits, X, groups: Sequence[Tuple[int, int, int]], weights: Sequence[Tuple], mark=False):
         """groups[g] = (expert, ord_lo, ord_hi); weights[g] = (W_gate, W_up, W_down). Returns Y."""
@@ -91,15 +107,7 @@ class RankLayer:
                         b.ws_permute)
         self._mark("permuted", mark)
         wg, wu, wd = ([w[i] for w in weights] for i in range(3))
-        B.feplb_grouped_ffn(b.Xp, b.offsets, 0, G, self.d, self.f, wg, wu, wd, b.H, b.Yp,
-                            phases=B.FFN_SCHEDULE, ws=b.ws_ffn)
-        self._mark("scheduled", mark)
-        B.feplb_grouped_ffn(b.Xp, b.offsets, 0, G, self.d, self.f, wg, wu, wd, b.H, b.Yp,
-                            phases=B.FFN_GATE_UP, ws=b.ws_ffn)
-        self._mark("gate_up_done", mark)
-        B.feplb_grouped_ffn(b.Xp, b.offsets, 0, G, self.d, self.f, wg, wu, wd, b.H, b.Yp,
-                            phases=B.FFN_DOWN, ws=b.ws_ffn)
-        self._mark("down_done", mark)
+        self._ffn_range(0, G, wg, wu, wd, "static", mark)
         B.feplb_unpermute_combine(b.Yp, b.inv, b.topk_w, self.T, self.k, self.d, b.Y)
         self._mark("combined", mark)
         return b.Y
@@ -133,6 +141,8 @@ class RankLayer:
         side = self.side_stream if overlap else main
         if overlap:
             side.wait_stream(main)
+        if mark and moves:
+            self.timeline.setdefault("copy_start", B.HipEvent()).record(side)
         for i, (e, *_rest) in enumerate(moves):
             last = i == len(moves) - 1
             B.feplb_stage_weights(b.slots[i], remote_sources[e], side, self.staged if last else None)
@@ -141,15 +151,11 @@ class RankLayer:
         self._mark("permuted", mark)
         wlist = [static_weights[e] for e in static] + [self.slot_views(i) for i in range(len(moves))]
         wg, wu, wd = ([w[i] for w in wlist] for i in range(3))
-        both = B.FFN_ALL
-        B.feplb_grouped_ffn(b.Xp, b.offsets, 0, Gs, self.d, self.f, wg, wu, wd, b.H, b.Yp, phases=both,
-                            ws=b.ws_ffn)
-        self._mark("static_done", mark)
+        self._ffn_range(0, Gs, wg, wu, wd, "static", mark)
         if moves:
             B.feplb_stream_wait(main, self.staged)
             self._mark("staged", mark)
-            B.feplb_grouped_ffn(b.Xp, b.offsets, Gs, G, self.d, self.f, wg, wu, wd, b.H, b.Yp, phases=both,
-                                ws=b.ws_ffn)
+            self._ffn_range(Gs, G, wg, wu, wd, "dynamic", mark)
         self._mark("dynamic_done", mark)
         B.feplb_unpermute_combine(b.Yp, b.inv, b.topk_w, self.T, self.k, self.d, b.Y)
         self._mark("combined", mark)
