@@ -6,16 +6,25 @@
 //   gate_up : H[r,:]  = bf16( silu(Xp[r,:] Wg[g]) * (Xp[r,:] Wu[g]) )
 //   down    : Yp[r,:] = H[r,:] Wd[g]
 // A small schedule kernel turns offsets[] (device memory, ragged, possibly
-// empty groups) into a table of 128-row tiles; the GEMM grid covers an upper
-// bound of tiles and surplus blocks leave at once, so the host never needs R.
+// empty groups) into a table of row tiles; the GEMM grid covers an upper bound
+// of tiles and surplus blocks leave at once, so the host never needs R.
 //
-// Tile: 128 rows x 256 weight columns x 64 k per step, 4 wavefronts (2 x 2),
-// each 64 x 128 as 2 x 4 MFMA 32x32x16 bf16 tiles with fp32 accumulators.  For
-// gate_up the 256 weight columns are 128 gate + the matching 128 up columns, so
-// the SwiGLU product happens in registers and only H is written.
-// Weights are row-major [K,N] (N contiguous) as the caller stores them; an MFMA
-// lane needs 8 consecutive k of one column, so each thread loads an 8(k) x 8(n)
-// block and transposes it in registers on the way into LDS.
+// Block tile: 256 rows x 256 weight columns x 64 k per step, 4 wavefronts
+// (2 x 2), one per SIMD, each 128 x 128 as 4 x 4 MFMA 32x32x16 bf16 tiles
+// (256 fp32 accumulators per lane).  For gate_up the 256 weight columns are
+// 128 gate + the matching 128 up columns, so the SwiGLU product happens in
+// registers and only H is written.  LDS holds two stages of (A 256 rows x 64 k,
+// k-contiguous, 144-byte pitch; B 64 k x 256 columns, column-contiguous as in
+// memory, 576-byte pitch); global loads for step kt+2 and the LDS fill of step
+// kt+1 overlap the MFMAs of step kt, one barrier per step.
+// Weights are row-major [K,N] (N contiguous) as the caller stores them, while
+// an MFMA lane needs 8 consecutive k of one column: the B fragments are read
+// with the transposing LDS load of gfx950 (ds_read_b64_tr_b16), which hands
+// lane i of a 16-lane group the 4 k-values of column i from a 4(k) x 16(n)
+// block, so no transpose is done in registers.
+// Blocks are mapped to tiles in 8 x 4 patches per XCD (workgroups are dealt
+// round-robin to the 8 XCDs, each with its own L2), so the 32 tiles an XCD
+// runs at a time share 8 row panels and 4 weight panels.
 #include "common.h"
 
 namespace {
@@ -23,12 +32,18 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef short i16x4 __attribute__((ext_vector_type(4)));
 
-constexpr int BM = 128;    // rows per tile
-constexpr int BNW = 256;   // weight columns per tile
-constexpr int BK = 64;     // k per step
-constexpr int LDK = BK + 8;  // LDS row pitch in bf16 (144 bytes: conflict-free 16-byte reads)
+constexpr int BM = 256;      // rows per tile
+constexpr int BNW = 256;     // weight columns per tile
+constexpr int BK = 64;       // k per step
+constexpr int LDK = BK + 8;    // A: LDS row pitch in bf16 (144 bytes: conflict-free 16-byte reads)
+constexpr int LDN = BNW + 32;  // B: LDS row pitch in bf16 (576 bytes: 4 consecutive rows cover all banks)
 constexpr int THREADS = 256;
+constexpr int A_ELEMS = BM * LDK;
+constexpr int STAGE_ELEMS = A_ELEMS + BK * LDN;             // bf16 elements per stage
+constexpr size_t LDS_BYTES = 2 * (size_t)STAGE_ELEMS * 2;   // two stages
+constexpr int XCDS = 8;
 
 struct WeightTable {
   const void* w0[FEPLB_MAX_GROUPS];  // gate (gate_up) or down (down)
@@ -76,105 +91,177 @@ __device__ __forceinline__ float silu(float a) { return a / (1.0f + __expf(-a));
 template <int MODE, bool OUT_BF16>
 __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
     const uint16_t* __restrict__ A, const int4* __restrict__ sched, int K, int N, int n_tiles_n,
-    WeightTable wt, void* __restrict__ out) {
-  __shared__ __attribute__((aligned(16))) uint16_t As[BM * LDK];
-  __shared__ __attribute__((aligned(16))) uint16_t Bs[BNW * LDK];
+    int patch_n, WeightTable wt, void* __restrict__ out) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
 
+  // ---- block -> tile: patches of (32 / patch_n) row tiles x patch_n column tiles per XCD
   const int tid = threadIdx.x;
-  const int nt = blockIdx.x % n_tiles_n;
-  const int mt = blockIdx.x / n_tiles_n;
+  const int xcd = blockIdx.x % XCDS;
+  const int slot = blockIdx.x / XCDS;
+  const int patch_m = 32 / patch_n;
+  const int patch = (slot / 32) * XCDS + xcd;
+  const int within = slot % 32;
+  const int patches_n = n_tiles_n / patch_n;
+  const int mt = (patch / patches_n) * patch_m + within % patch_m;
+  const int nt = (patch % patches_n) * patch_n + within / patch_m;
   if (mt >= sched[0].x) return;
   const int4 tile = sched[1 + mt];
   const int g = tile.x, row0 = tile.y, rows = tile.z;
 
   // ---- global -> register staging
-  // A: 128 rows x 8 vectors of 8 bf16; thread handles vectors tid + 256*i
-  const uint16_t* a_src[4];
+  // A: 256 rows x 8 vectors of 8 bf16; thread handles row tid/8 + 32*i, vector tid%8
+  const int a_vec = tid % 8;
+  uint32_t a_off[8];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int idx = tid + THREADS * i;
-    const int r = min(idx / 8, rows - 1);
-    a_src[i] = A + (size_t)(row0 + r) * K + (idx % 8) * 8;
+  for (int i = 0; i < 8; ++i) {
+    const int r = min(tid / 8 + 32 * i, rows - 1);
+    a_off[i] = (uint32_t)r * (uint32_t)K + a_vec * 8;
   }
-  // B: thread owns the 8(k) x 8(n) block (kb, nb)
-  const int kb = tid % 8, nb = tid / 8;
+  const uint16_t* a_base = A + (size_t)row0 * K;
+  // B: 64 k-rows x 32 vectors of 8 columns; thread handles k-row tid/32 + 8*i, vector tid%32
+  // (a wavefront reads 2 rows x 512 contiguous bytes per load)
+  const int b_vec = tid % 32, b_k = tid / 32;
   const uint16_t* b_src;
   if (MODE == 0) {
-    const uint16_t* W = (const uint16_t*)(nb < 16 ? wt.w0[g] : wt.w1[g]);
-    b_src = W + (size_t)(kb * 8) * N + (size_t)nt * 128 + (nb % 16) * 8;
+    const uint16_t* W = (const uint16_t*)(b_vec < 16 ? wt.w0[g] : wt.w1[g]);
+    b_src = W + (size_t)b_k * N + (size_t)nt * 128 + (b_vec % 16) * 8;
   } else {
-    b_src = (const uint16_t*)wt.w0[g] + (size_t)(kb * 8) * N + (size_t)nt * 256 + nb * 8;
+    b_src = (const uint16_t*)wt.w0[g] + (size_t)b_k * N + (size_t)nt * 256 + b_vec * 8;
   }
 
-  u32x4 a_reg[4], b_reg[8];
-  auto load_tiles = [&](int k0) {
+  u32x4 a_reg[8], b_reg[8];
+  auto load_a = [&](int k0) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) a_reg[i] = *(const u32x4*)(a_src[i] + k0);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) b_reg[i] = *(const u32x4*)(b_src + (size_t)(k0 + i) * N);
+    for (int i = 0; i < 8; ++i) a_reg[i] = *(const u32x4*)(a_base + a_off[i] + k0);
   };
-  auto store_tiles = [&]() {
+  auto load_b = [&](int k0) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int idx = tid + THREADS * i;
-      *(u32x4*)(As + (idx / 8) * LDK + (idx % 8) * 8) = a_reg[i];
-    }
+    for (int i = 0; i < 8; ++i) b_reg[i] = *(const u32x4*)(b_src + (size_t)(k0 + 8 * i) * N);
+  };
+  auto store_a = [&](uint16_t* As) {
 #pragma unroll
-    for (int c = 0; c < 8; ++c) {
-      u32x4 o;
+    for (int i = 0; i < 8; ++i)
+      *(u32x4*)(As + (tid / 8 + 32 * i) * LDK + a_vec * 8) = a_reg[i];
+  };
+  // rows i0..i0+3 of the thread's share of the B tile, layout unchanged
+  auto store_b_half = [&](uint16_t* Bs, int i0) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const uint32_t lo = b_reg[2 * j][c / 2], hi = b_reg[2 * j + 1][c / 2];
-        o[j] = (c & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16));
-      }
-      *(u32x4*)(Bs + (nb * 8 + c) * LDK + kb * 8) = o;
-    }
+    for (int i = i0; i < i0 + 4; ++i) *(u32x4*)(Bs + (b_k + 8 * i) * LDN + b_vec * 8) = b_reg[i];
   };
 
-  // ---- wave tiling
+  // ---- wave tiling: 2 x 2 waves, each 128 rows x 128 weight columns
   const int wave = tid / 64, lane = tid % 64;
   const int wm = wave / 2, wn = wave % 2;
   const int l32 = lane % 32, lk = (lane / 32) * 8;
-  int b_row[4];
+  int a_row[4], b_col[4];
+#pragma unroll
+  for (int mi = 0; mi < 4; ++mi) a_row[mi] = (wm * 128 + mi * 32 + l32) * LDK + lk;
+  // transposing read: lane s of a 16-lane group addresses 4 columns of k-row s/4; the group
+  // then holds column (lane % 16) of its 16-column block, k = 4 consecutive rows
+  const int tr_row = (lane / 32) * 8 + (lane % 16) / 4;
+  const int tr_col = ((lane / 16) % 2) * 16 + (lane % 4) * 4;
 #pragma unroll
   for (int nj = 0; nj < 4; ++nj) {
-    if (MODE == 0)
-      b_row[nj] = (nj / 2) * 128 + wn * 64 + (nj % 2) * 32 + l32;
-    else
-      b_row[nj] = wn * 128 + nj * 32 + l32;
+    const int c = MODE == 0 ? (nj / 2) * 128 + wn * 64 + (nj % 2) * 32 : wn * 128 + nj * 32;
+    b_col[nj] = A_ELEMS + tr_row * LDN + c + tr_col;
   }
 
-  f32x16 acc[2][4];
+  f32x16 acc[4][4];
 #pragma unroll
-  for (int mi = 0; mi < 2; ++mi)
+  for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
     for (int nj = 0; nj < 4; ++nj)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[mi][nj][v] = 0.f;
 
-  const int KT = K / BK;
-  load_tiles(0);
-  for (int kt = 0; kt < KT; ++kt) {
-    __syncthreads();
-    store_tiles();
-    __syncthreads();
-    if (kt + 1 < KT) load_tiles((kt + 1) * BK);
+  bf16x8 af[2][4], bfr[2][4];
+  auto load_frags = [&](const uint16_t* S, int ks, int buf) {
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 af[2], bfr[4];
+    for (int mi = 0; mi < 4; ++mi) af[buf][mi] = *(const bf16x8*)(S + a_row[mi] + ks * 16);
 #pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
-        af[mi] = *(const bf16x8*)(As + (wm * 64 + mi * 32 + l32) * LDK + ks * 16 + lk);
+    for (int nj = 0; nj < 4; ++nj) {
+      typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
+      const uint16_t* p = S + b_col[nj] + ks * 16 * LDN;
+      const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)p);
+      const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(p + 4 * LDN));
+      bfr[buf][nj] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    }
+  };
+  auto mfma16 = [&](int buf) {
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
       for (int nj = 0; nj < 4; ++nj)
-        bfr[nj] = *(const bf16x8*)(Bs + b_row[nj] * LDK + ks * 16 + lk);
+        acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][mi], bfr[buf][nj],
+                                                             acc[mi][nj], 0, 0, 0);
+  };
+
+  // Software pipeline.  Step kt computes from stage kt&1 while the registers
+  // holding tile kt+1 are written to the other stage and tile kt+2 is fetched.
+  // Loads past the end re-read the last tile (k clamped) and the matching LDS
+  // fill goes to a stage nobody reads again, so the loop body has no branches
+  // and the interleaving below applies to every step.
+  const int KT = K / BK;
+  const int k_last = K - BK;
+  load_a(0);
+  load_b(0);
+  store_a(lds);
+  store_b_half(lds + A_ELEMS, 0);
+  store_b_half(lds + A_ELEMS, 4);
+  load_a(min(BK, k_last));
+  load_b(min(BK, k_last));
+  __syncthreads();
+  load_frags(lds, 0, 0);
+  for (int kt = 0; kt < KT; ++kt) {
+    const uint16_t* S = lds + (kt & 1) * STAGE_ELEMS;
+    uint16_t* Sn = lds + ((kt + 1) & 1) * STAGE_ELEMS;
+    const int k2 = min((kt + 2) * BK, k_last);
+    // section 0: fragments of k-slice 1; first half of the B tile of step kt+1 -> LDS
+    load_frags(S, 1, 1);
+    store_b_half(Sn + A_ELEMS, 0);
+    mfma16(0);
 #pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-        for (int nj = 0; nj < 4; ++nj)
-          acc[mi][nj] =
-              __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[nj], acc[mi][nj], 0, 0, 0);
+    for (int i = 0; i < 16; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+      __builtin_amdgcn_sched_group_barrier(0x180, 1, 0);   // 1 LDS op
     }
+    __builtin_amdgcn_sched_barrier(0);
+    // section 1: fragments of k-slice 2; second half of the B tile -> LDS; its
+    // registers are free again: fetch the B tile of step kt+2 (a full step ahead of its use)
+    load_frags(S, 2, 0);
+    store_b_half(Sn + A_ELEMS, 4);
+    load_b(k2);
+    mfma16(1);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x180, 1, 0);
+      if (i >= 8) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // 1 global load
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // section 2: fragments of k-slice 3; A tile of step kt+1 -> LDS, then fetch the A tile of step kt+2
+    load_frags(S, 3, 1);
+    store_a(Sn);
+    load_a(k2);
+    mfma16(0);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x180, 1, 0);
+      if (i >= 8) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // every wave has finished reading stage kt&1 and writing the other one
+    __syncthreads();
+    // section 3: first fragments of step kt+1
+    load_frags(Sn, 0, 0);
+    mfma16(1);
+#pragma unroll
+    for (int i = 0; i < 12; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
   }
 
   // ---- epilogue: lane holds column l32 of each 32x32 tile, rows 8*(v/4) + 4*(lane/32) + v%4
@@ -182,13 +269,13 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
   if (MODE == 0) {
     uint16_t* H = (uint16_t*)out;
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
+    for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
       for (int nj = 0; nj < 2; ++nj) {
         const int col = nt * 128 + wn * 64 + nj * 32 + l32;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const int r = wm * 64 + mi * 32 + 8 * (v / 4) + rsub + (v % 4);
+          const int r = wm * 128 + mi * 32 + 8 * (v / 4) + rsub + (v % 4);
           if (r < rows) {
             const float h = silu(acc[mi][nj][v]) * acc[mi][nj + 2][v];
             H[(size_t)(row0 + r) * N + col] = (uint16_t)bf16_rne(h);
@@ -197,13 +284,13 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
       }
   } else {
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
+    for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
       for (int nj = 0; nj < 4; ++nj) {
         const int col = nt * 256 + wn * 128 + nj * 32 + l32;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const int r = wm * 64 + mi * 32 + 8 * (v / 4) + rsub + (v % 4);
+          const int r = wm * 128 + mi * 32 + 8 * (v / 4) + rsub + (v % 4);
           if (r < rows) {
             if (OUT_BF16)
               ((uint16_t*)out)[(size_t)(row0 + r) * N + col] = (uint16_t)bf16_rne(acc[mi][nj][v]);
@@ -216,6 +303,24 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
 }
 
 int max_tiles_for(int R_cap, int ng) { return R_cap / BM + ng + 1; }
+
+template <int MODE, bool OUT_BF16>
+hipError_t launch_gemm(const void* A, const int4* sched, int K, int N, int n_tiles_n, int max_tiles,
+                       const WeightTable& wt, void* out, hipStream_t s) {
+  static hipError_t attr = hipFuncSetAttribute(
+      reinterpret_cast<const void*>(&grouped_gemm_kernel<MODE, OUT_BF16>),
+      hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES);
+  if (attr != hipSuccess) return attr;
+  const int patch_n = n_tiles_n % 4 == 0 ? 4 : (n_tiles_n % 2 == 0 ? 2 : 1);
+  const int patch_m = 32 / patch_n;
+  const int patches_m = (max_tiles + patch_m - 1) / patch_m;
+  const int patches = patches_m * (n_tiles_n / patch_n);
+  const int patch_rounds = (patches + XCDS - 1) / XCDS;
+  const unsigned blocks = (unsigned)patch_rounds * XCDS * 32;
+  hipLaunchKernelGGL((grouped_gemm_kernel<MODE, OUT_BF16>), dim3(blocks), dim3(THREADS), LDS_BYTES,
+                     s, (const uint16_t*)A, sched, K, N, n_tiles_n, patch_n, wt, out);
+  return hipGetLastError();
+}
 
 }  // namespace
 
@@ -283,23 +388,13 @@ extern "C" int32_t feplb_grouped_ffn(const void* Xp, const int32_t* offsets, int
     FEPLB_LAUNCH_CHECK("ffn_schedule_kernel");
   }
   if (do_up) {
-    const int ntn = f / 128;
-    hipLaunchKernelGGL((grouped_gemm_kernel<0, true>), dim3((unsigned)max_tiles * ntn),
-                       dim3(THREADS), 0, s, (const uint16_t*)Xp, (const int4*)ws, d, f, ntn, up_tab,
-                       H);
-    FEPLB_LAUNCH_CHECK("grouped_gemm_kernel<gate_up>");
+    FEPLB_HIP((launch_gemm<0, true>(Xp, (const int4*)ws, d, f, f / 128, max_tiles, up_tab, H, s)));
   }
   if (do_down) {
-    const int ntn = d / 256;
     if (yp_dtype == FEPLB_BF16)
-      hipLaunchKernelGGL((grouped_gemm_kernel<1, true>), dim3((unsigned)max_tiles * ntn),
-                         dim3(THREADS), 0, s, (const uint16_t*)H, (const int4*)ws, f, d, ntn,
-                         down_tab, Yp);
+      FEPLB_HIP((launch_gemm<1, true>(H, (const int4*)ws, f, d, d / 256, max_tiles, down_tab, Yp, s)));
     else
-      hipLaunchKernelGGL((grouped_gemm_kernel<1, false>), dim3((unsigned)max_tiles * ntn),
-                         dim3(THREADS), 0, s, (const uint16_t*)H, (const int4*)ws, f, d, ntn,
-                         down_tab, Yp);
-    FEPLB_LAUNCH_CHECK("grouped_gemm_kernel<down>");
+      FEPLB_HIP((launch_gemm<1, false>(H, (const int4*)ws, f, d, d / 256, max_tiles, down_tab, Yp, s)));
   }
   return FEPLB_OK;
 }
