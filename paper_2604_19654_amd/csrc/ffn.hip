@@ -14,9 +14,10 @@
 // (256 fp32 accumulators per lane).  For gate_up the 256 weight columns are
 // 128 gate + the matching 128 up columns, so the SwiGLU product happens in
 // registers and only H is written.  LDS holds two stages of (A 256 rows x 64 k,
-// k-contiguous, 144-byte pitch; B 64 k x 256 columns, column-contiguous as in
-// memory, 576-byte pitch); global loads for step kt+2 and the LDS fill of step
-// kt+1 overlap the MFMAs of step kt, one barrier per step.
+// k-contiguous; B 64 k x 256 columns, column-contiguous as in memory), filled
+// by LDS-DMA loads (global_load_lds_dwordx4: HBM/L2 -> LDS without passing
+// through registers) with XOR-swizzled layouts instead of padding; the loads of
+// step kt+2 overlap the MFMAs of steps kt and kt+1, one barrier per step.
 // Weights are row-major [K,N] (N contiguous) as the caller stores them, while
 // an MFMA lane needs 8 consecutive k of one column: the B fragments are read
 // with the transposing LDS load of gfx950 (ds_read_b64_tr_b16), which hands
@@ -25,6 +26,7 @@
 // Blocks are mapped to tiles in 8 x 4 patches per XCD (workgroups are dealt
 // round-robin to the 8 XCDs, each with its own L2), so the 32 tiles an XCD
 // runs at a time share 8 row panels and 4 weight panels.
+#include <type_traits>
 #include "common.h"
 
 namespace {
@@ -33,16 +35,17 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef short i16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(1))) const void gptr_t;
+typedef __attribute__((address_space(3))) void lptr_t;
 
 constexpr int BM = 256;      // rows per tile
 constexpr int BNW = 256;     // weight columns per tile
 constexpr int BK = 64;       // k per step
-constexpr int LDK = BK + 8;    // A: LDS row pitch in bf16 (144 bytes: conflict-free 16-byte reads)
-constexpr int LDN = BNW + 32;  // B: LDS row pitch in bf16 (576 bytes: 4 consecutive rows cover all banks)
 constexpr int THREADS = 256;
-constexpr int A_ELEMS = BM * LDK;
-constexpr int STAGE_ELEMS = A_ELEMS + BK * LDN;             // bf16 elements per stage
-constexpr size_t LDS_BYTES = 2 * (size_t)STAGE_ELEMS * 2;   // two stages
+// LDS: two A stages and two B stages of 32 KB each; a B stage is two parts of 64 k-rows x 256 bytes.
+constexpr int A_STAGE_BYTES = BM * BK * 2;
+constexpr int B_PART_BYTES = BK * 128 * 2;
+constexpr int B_STAGE_BYTES = 2 * B_PART_BYTES;
 constexpr int XCDS = 8;
 
 struct WeightTable {
@@ -92,7 +95,13 @@ template <int MODE, bool OUT_BF16>
 __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
     const uint16_t* __restrict__ A, const int4* __restrict__ sched, int K, int N, int n_tiles_n,
     int patch_n, WeightTable wt, void* __restrict__ out) {
-  extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
+  // Four separate LDS arrays (not one block with run-time offsets): the compiler can then prove
+  // that an LDS-DMA load into one stage and the fragment reads of the other stage do not alias,
+  // and does not make the reads wait for the loads just issued.
+  __shared__ __attribute__((aligned(1024))) char lds_a0[A_STAGE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char lds_a1[A_STAGE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char lds_b0[B_STAGE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char lds_b1[B_STAGE_BYTES];
 
   // ---- block -> tile: patches of (32 / patch_n) row tiles x patch_n column tiles per XCD
   const int tid = threadIdx.x;
@@ -108,62 +117,74 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
   const int4 tile = sched[1 + mt];
   const int g = tile.x, row0 = tile.y, rows = tile.z;
 
-  // ---- global -> register staging
-  // A: 256 rows x 8 vectors of 8 bf16; thread handles row tid/8 + 32*i, vector tid%8
-  const int a_vec = tid % 8;
-  uint32_t a_off[8];
+  // ---- global -> LDS, directly (LDS-DMA loads: no register staging, no LDS store instructions)
+  // A wavefront-wide 16-byte load writes 1 KB of contiguous LDS, lane l at byte 16*l, so the
+  // LDS layouts are swizzled through the choice of the global address each lane reads.
+  const int wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64;
+  // A stage: 256 rows x 128 bytes (64 k).  Load i of wave w fills rows 64w + 8i .. +7; the lane
+  // at 16-byte slot p of row r holds k-chunk p ^ ((r >> 1) & 7), which makes the 16-byte
+  // fragment reads of 16 consecutive rows hit 16 different bank groups.
+  uint32_t a_goff[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    const int r = min(tid / 8 + 32 * i, rows - 1);
-    a_off[i] = (uint32_t)r * (uint32_t)K + a_vec * 8;
+    const int r = wave * 64 + i * 8 + lane / 8;
+    const int chunk = (lane % 8) ^ ((r >> 1) & 7);
+    a_goff[i] = ((uint32_t)min(r, rows - 1) * (uint32_t)K + chunk * 8) * 2;
   }
-  const uint16_t* a_base = A + (size_t)row0 * K;
-  // B: 64 k-rows x 32 vectors of 8 columns; thread handles k-row tid/32 + 8*i, vector tid%32
-  // (a wavefront reads 2 rows x 512 contiguous bytes per load)
-  const int b_vec = tid % 32, b_k = tid / 32;
-  const uint16_t* b_src;
-  if (MODE == 0) {
-    const uint16_t* W = (const uint16_t*)(b_vec < 16 ? wt.w0[g] : wt.w1[g]);
-    b_src = W + (size_t)b_k * N + (size_t)nt * 128 + (b_vec % 16) * 8;
-  } else {
-    b_src = (const uint16_t*)wt.w0[g] + (size_t)b_k * N + (size_t)nt * 256 + b_vec * 8;
-  }
+  const char* a_gbase = (const char*)(A + (size_t)row0 * K);
+  // B stage: two parts (gate | up, or the two column halves) of 64 k-rows x 256 bytes (128
+  // columns).  Waves 0,1 fill part 0, waves 2,3 part 1; load i fills k-rows 4q .. 4q+3,
+  // q = 8*(w%2) + i.  Inside a row the four 64-byte groups are XOR-ed with (row & 3) so that
+  // the transposing reads of 4 consecutive k-rows cover all banks.
+  const int part = wave / 2;
+  const int b_r = lane / 16;                       // k-row inside the load (= row & 3)
+  const int b_slot = ((((lane % 16) >> 2) ^ b_r) << 2) | (lane & 3);   // 16-byte column slot read
+  const uint32_t b_goff = ((uint32_t)((wave % 2) * 32 + b_r) * (uint32_t)N + b_slot * 8) * 2;
+  const char* b_gbase;
+  if (MODE == 0)
+    b_gbase = (const char*)((const uint16_t*)(part ? wt.w1[g] : wt.w0[g]) + (size_t)nt * 128);
+  else
+    b_gbase = (const char*)((const uint16_t*)wt.w0[g] + (size_t)nt * 256 + part * 128);
+  const size_t b_row_bytes = (size_t)N * 2;
 
-  u32x4 a_reg[8], b_reg[8];
-  auto load_a = [&](int k0) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) a_reg[i] = *(const u32x4*)(a_base + a_off[i] + k0);
-  };
-  auto load_b = [&](int k0) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) b_reg[i] = *(const u32x4*)(b_src + (size_t)(k0 + 8 * i) * N);
-  };
-  auto store_a = [&](uint16_t* As) {
+  auto issue_loads = [&](auto stage, int k0) {
+    char* a_dst = (stage.value ? lds_a1 : lds_a0) + wave * 8192;
+    char* b_dst = (stage.value ? lds_b1 : lds_b0) + part * B_PART_BYTES + (wave % 2) * 8192;
+    const char* ag = a_gbase + (size_t)k0 * 2;
+    const char* bg = b_gbase + (size_t)k0 * b_row_bytes;
 #pragma unroll
     for (int i = 0; i < 8; ++i)
-      *(u32x4*)(As + (tid / 8 + 32 * i) * LDK + a_vec * 8) = a_reg[i];
-  };
-  // rows i0..i0+3 of the thread's share of the B tile, layout unchanged
-  auto store_b_half = [&](uint16_t* Bs, int i0) {
+      __builtin_amdgcn_global_load_lds((gptr_t*)(ag + a_goff[i]), (lptr_t*)(a_dst + i * 1024), 16, 0, 0);
 #pragma unroll
-    for (int i = i0; i < i0 + 4; ++i) *(u32x4*)(Bs + (b_k + 8 * i) * LDN + b_vec * 8) = b_reg[i];
+    for (int i = 0; i < 8; ++i)
+      __builtin_amdgcn_global_load_lds((gptr_t*)(bg + (size_t)i * 4 * b_row_bytes + b_goff),
+                                       (lptr_t*)(b_dst + i * 1024), 16, 0, 0);
   };
 
   // ---- wave tiling: 2 x 2 waves, each 128 rows x 128 weight columns
-  const int wave = tid / 64, lane = tid % 64;
   const int wm = wave / 2, wn = wave % 2;
-  const int l32 = lane % 32, lk = (lane / 32) * 8;
-  int a_row[4], b_col[4];
+  const int l32 = lane % 32, h = lane / 32;
+  // A fragment (mi, ks): row wm*128 + mi*32 + l32, k-chunk 2*ks + h, at its swizzled slot
+  uint32_t a_addr[4][4];
 #pragma unroll
-  for (int mi = 0; mi < 4; ++mi) a_row[mi] = (wm * 128 + mi * 32 + l32) * LDK + lk;
-  // transposing read: lane s of a 16-lane group addresses 4 columns of k-row s/4; the group
-  // then holds column (lane % 16) of its 16-column block, k = 4 consecutive rows
-  const int tr_row = (lane / 32) * 8 + (lane % 16) / 4;
-  const int tr_col = ((lane / 16) % 2) * 16 + (lane % 4) * 4;
+  for (int mi = 0; mi < 4; ++mi) {
+    const int r = wm * 128 + mi * 32 + l32;
 #pragma unroll
-  for (int nj = 0; nj < 4; ++nj) {
-    const int c = MODE == 0 ? (nj / 2) * 128 + wn * 64 + (nj % 2) * 32 : wn * 128 + nj * 32;
-    b_col[nj] = A_ELEMS + tr_row * LDN + c + tr_col;
+    for (int ks = 0; ks < 4; ++ks) a_addr[mi][ks] = r * 128 + (((2 * ks + h) ^ ((r >> 1) & 7)) * 16);
+  }
+  // B fragment (nj, ks): transposing read; lane s of a 16-lane group addresses 4 columns of
+  // k-row s/4 and ends up with the 4 k-values of column (lane % 16) of the 16-column block
+  uint32_t b_addr[4];
+  {
+    const int tr_r = h * 8 + (lane % 16) / 4;      // k-row inside the 16-row slice (ks adds 16, the second read 4)
+#pragma unroll
+    for (int nj = 0; nj < 4; ++nj) {
+      const int prt = MODE == 0 ? nj / 2 : wn;
+      const int col = (MODE == 0 ? wn * 64 + (nj % 2) * 32 : nj * 32) + ((lane / 16) % 2) * 16 + (lane % 4) * 4;
+      const int slot = col / 8;
+      const int sw = ((((slot >> 2) ^ (tr_r & 3)) << 2) | (slot & 3));
+      b_addr[nj] = prt * B_PART_BYTES + tr_r * 256 + sw * 16 + (col % 8) * 2;
+    }
   }
 
   f32x16 acc[4][4];
@@ -175,15 +196,17 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
       for (int v = 0; v < 16; ++v) acc[mi][nj][v] = 0.f;
 
   bf16x8 af[2][4], bfr[2][4];
-  auto load_frags = [&](const uint16_t* S, int ks, int buf) {
+  auto load_frags = [&](auto stage, int ks, int buf) {
+    const char* sa = stage.value ? lds_a1 : lds_a0;
+    const char* sb = (stage.value ? lds_b1 : lds_b0) + ks * 16 * 256;
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi) af[buf][mi] = *(const bf16x8*)(S + a_row[mi] + ks * 16);
+    for (int mi = 0; mi < 4; ++mi) af[buf][mi] = *(const bf16x8*)(sa + a_addr[mi][ks]);
 #pragma unroll
     for (int nj = 0; nj < 4; ++nj) {
       typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
-      const uint16_t* p = S + b_col[nj] + ks * 16 * LDN;
+      const char* p = sb + b_addr[nj];
       const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)p);
-      const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(p + 4 * LDN));
+      const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(p + 4 * 256));
       bfr[buf][nj] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     }
   };
@@ -196,65 +219,25 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
                                                              acc[mi][nj], 0, 0, 0);
   };
 
-  // Software pipeline.  Step kt computes from stage kt&1 while the registers
-  // holding tile kt+1 are written to the other stage and tile kt+2 is fetched.
-  // Loads past the end re-read the last tile (k clamped) and the matching LDS
-  // fill goes to a stage nobody reads again, so the loop body has no branches
-  // and the interleaving below applies to every step.
-  const int KT = K / BK;
+  // Software pipeline.  Step kt computes from stage kt&1.  Once every wave has passed the
+  // barrier that ends the reads of a stage, the loads of the tile two steps ahead are issued
+  // into it; they have a whole step to land before the barrier that precedes their use.
+  // Loads past the end re-read the last tile (k clamped) into a stage nobody reads again, so
+  // the loop body has no branches.
+  const int KT = K / BK;   // even: K is a multiple of 128
   const int k_last = K - BK;
-  load_a(0);
-  load_b(0);
-  store_a(lds);
-  store_b_half(lds + A_ELEMS, 0);
-  store_b_half(lds + A_ELEMS, 4);
-  load_a(min(BK, k_last));
-  load_b(min(BK, k_last));
-  __syncthreads();
-  load_frags(lds, 0, 0);
-  for (int kt = 0; kt < KT; ++kt) {
-    const uint16_t* S = lds + (kt & 1) * STAGE_ELEMS;
-    uint16_t* Sn = lds + ((kt + 1) & 1) * STAGE_ELEMS;
-    const int k2 = min((kt + 2) * BK, k_last);
-    // section 0: fragments of k-slice 1; first half of the B tile of step kt+1 -> LDS
-    load_frags(S, 1, 1);
-    store_b_half(Sn + A_ELEMS, 0);
+  constexpr std::integral_constant<int, 0> st0{};
+  constexpr std::integral_constant<int, 1> st1{};
+  auto step = [&](auto cur, auto nxt, int k2) {
+    load_frags(cur, 1, 1);
     mfma16(0);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
+    for (int i = 0; i < 12; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
-      __builtin_amdgcn_sched_group_barrier(0x180, 1, 0);   // 1 LDS op
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
     }
     __builtin_amdgcn_sched_barrier(0);
-    // section 1: fragments of k-slice 2; second half of the B tile -> LDS; its
-    // registers are free again: fetch the B tile of step kt+2 (a full step ahead of its use)
-    load_frags(S, 2, 0);
-    store_b_half(Sn + A_ELEMS, 4);
-    load_b(k2);
-    mfma16(1);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x180, 1, 0);
-      if (i >= 8) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // 1 global load
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    // section 2: fragments of k-slice 3; A tile of step kt+1 -> LDS, then fetch the A tile of step kt+2
-    load_frags(S, 3, 1);
-    store_a(Sn);
-    load_a(k2);
-    mfma16(0);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x180, 1, 0);
-      if (i >= 8) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    // every wave has finished reading stage kt&1 and writing the other one
-    __syncthreads();
-    // section 3: first fragments of step kt+1
-    load_frags(Sn, 0, 0);
+    load_frags(cur, 2, 0);
     mfma16(1);
 #pragma unroll
     for (int i = 0; i < 12; ++i) {
@@ -262,7 +245,38 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
+    load_frags(cur, 3, 1);
+    mfma16(0);
+#pragma unroll
+    for (int i = 0; i < 12; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // all reads of stage `cur` are done and the next tile has landed in the other stage
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    issue_loads(cur, k2);
+    load_frags(nxt, 0, 0);
+    mfma16(1);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // 1 global->LDS load
+      if (i < 12) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  issue_loads(st0, 0);
+  issue_loads(st1, min(BK, k_last));
+  __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): both tiles have landed
+  __syncthreads();
+  load_frags(st0, 0, 0);
+  for (int kt = 0; kt < KT; kt += 2) {
+    step(st0, st1, min((kt + 2) * BK, k_last));
+    step(st1, st0, min((kt + 3) * BK, k_last));
   }
+  __builtin_amdgcn_s_waitcnt(0);   // the clamped trailing loads must land before the block ends
 
   // ---- epilogue: lane holds column l32 of each 32x32 tile, rows 8*(v/4) + 4*(lane/32) + v%4
   const int rsub = (lane / 32) * 4;
@@ -307,17 +321,13 @@ int max_tiles_for(int R_cap, int ng) { return R_cap / BM + ng + 1; }
 template <int MODE, bool OUT_BF16>
 hipError_t launch_gemm(const void* A, const int4* sched, int K, int N, int n_tiles_n, int max_tiles,
                        const WeightTable& wt, void* out, hipStream_t s) {
-  static hipError_t attr = hipFuncSetAttribute(
-      reinterpret_cast<const void*>(&grouped_gemm_kernel<MODE, OUT_BF16>),
-      hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES);
-  if (attr != hipSuccess) return attr;
   const int patch_n = n_tiles_n % 4 == 0 ? 4 : (n_tiles_n % 2 == 0 ? 2 : 1);
   const int patch_m = 32 / patch_n;
   const int patches_m = (max_tiles + patch_m - 1) / patch_m;
   const int patches = patches_m * (n_tiles_n / patch_n);
   const int patch_rounds = (patches + XCDS - 1) / XCDS;
   const unsigned blocks = (unsigned)patch_rounds * XCDS * 32;
-  hipLaunchKernelGGL((grouped_gemm_kernel<MODE, OUT_BF16>), dim3(blocks), dim3(THREADS), LDS_BYTES,
+  hipLaunchKernelGGL((grouped_gemm_kernel<MODE, OUT_BF16>), dim3(blocks), dim3(THREADS), 0,
                      s, (const uint16_t*)A, sched, K, N, n_tiles_n, patch_n, wt, out);
   return hipGetLastError();
 }
@@ -343,6 +353,7 @@ extern "C" int32_t feplb_grouped_ffn(const void* Xp, const int32_t* offsets, int
                 "grouped_ffn: phases=%d", phases);
   FEPLB_REQUIRE(yp_dtype == FEPLB_F32 || yp_dtype == FEPLB_BF16, FEPLB_EINVAL,
                 "grouped_ffn: unknown yp_dtype %d", yp_dtype);
+  // (both k extents, d and f, are then multiples of 128: the k loop runs two 64-wide steps per trip)
   FEPLB_REQUIRE(d % 256 == 0 && f % 128 == 0 && d > 0 && f > 0, FEPLB_ESHAPE,
                 "grouped_ffn: need d %% 256 == 0 and f %% 128 == 0 (d=%d f=%d)", d, f);
   const int ng = g_end - g_begin;
