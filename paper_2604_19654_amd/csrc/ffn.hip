@@ -9,15 +9,15 @@
 // empty groups) into a table of row tiles; the GEMM grid covers an upper bound
 // of tiles and surplus blocks leave at once, so the host never needs R.
 //
-// Block tile: 256 rows x 256 weight columns x 64 k per step, 4 wavefronts
+// Block tile: 256 rows x 256 weight columns x 32 k per step, 4 wavefronts
 // (2 x 2), one per SIMD, each 128 x 128 as 4 x 4 MFMA 32x32x16 bf16 tiles
 // (256 fp32 accumulators per lane).  For gate_up the 256 weight columns are
 // 128 gate + the matching 128 up columns, so the SwiGLU product happens in
-// registers and only H is written.  LDS holds two stages of (A 256 rows x 64 k,
-// k-contiguous; B 64 k x 256 columns, column-contiguous as in memory), filled
+// registers and only H is written.  LDS holds four stages of (A 256 rows x 32 k,
+// k-contiguous; B 32 k x 256 columns, column-contiguous as in memory), filled
 // by LDS-DMA loads (global_load_lds_dwordx4: HBM/L2 -> LDS without passing
-// through registers) with XOR-swizzled layouts instead of padding; the loads of
-// step kt+2 overlap the MFMAs of steps kt and kt+1, one barrier per step.
+// through registers) with XOR-swizzled layouts instead of padding; a tile is
+// requested three steps before its use, one barrier per step.
 // Weights are row-major [K,N] (N contiguous) as the caller stores them, while
 // an MFMA lane needs 8 consecutive k of one column: the B fragments are read
 // with the transposing LDS load of gfx950 (ds_read_b64_tr_b16), which hands
@@ -40,13 +40,29 @@ typedef __attribute__((address_space(3))) void lptr_t;
 
 constexpr int BM = 256;      // rows per tile
 constexpr int BNW = 256;     // weight columns per tile
-constexpr int BK = 64;       // k per step
+constexpr int BK = 32;       // k per step
+constexpr int NS = 4;        // LDS stages
 constexpr int THREADS = 256;
-// LDS: two A stages and two B stages of 32 KB each; a B stage is two parts of 64 k-rows x 256 bytes.
+// LDS: NS A stages and NS B stages of 16 KB each; a B stage is two parts of 32 k-rows x 256 bytes.
 constexpr int A_STAGE_BYTES = BM * BK * 2;
 constexpr int B_PART_BYTES = BK * 128 * 2;
 constexpr int B_STAGE_BYTES = 2 * B_PART_BYTES;
 constexpr int XCDS = 8;
+
+// 16-byte-per-lane load from global memory straight into LDS (LDS-DMA): lane l's data lands at
+// LDS byte address lds_base + 16*l (lds_base is wave-uniform and travels in M0).  Written as
+// inline assembly so that the loads' completion is tracked by the explicit s_waitcnt vmcnt(n)
+// of the pipeline below: the compiler's own tracking would wait for ALL outstanding loads
+// before any LDS read in a loop, i.e. also for the tiles requested for later steps.
+__device__ __forceinline__ void load_to_lds_16(const void* gptr, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
+               :
+               : "v"(gptr), "s"(lds_base)
+               : "memory", "m0");
+}
+__device__ __forceinline__ uint32_t lds_offset(const void* p) {
+  return (uint32_t)(uintptr_t)p;   // low half of a generic LDS address is the LDS byte offset
+}
 
 struct WeightTable {
   const void* w0[FEPLB_MAX_GROUPS];  // gate (gate_up) or down (down)
@@ -93,15 +109,25 @@ __device__ __forceinline__ float silu(float a) { return a / (1.0f + __expf(-a));
 // MODE 0: gate_up (+SwiGLU, bf16 out); MODE 1: down (fp32 or bf16 out)
 template <int MODE, bool OUT_BF16>
 __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
-    const uint16_t* __restrict__ A, const int4* __restrict__ sched, int K, int N, int n_tiles_n,
-    int patch_n, WeightTable wt, void* __restrict__ out) {
-  // Four separate LDS arrays (not one block with run-time offsets): the compiler can then prove
-  // that an LDS-DMA load into one stage and the fragment reads of the other stage do not alias,
-  // and does not make the reads wait for the loads just issued.
+    const uint16_t* __restrict__ A, int lda, const int4* __restrict__ sched, int K, int N,
+    int n_tiles_n, int patch_n, WeightTable wt, void* __restrict__ out, int ldo) {
+  // Separate LDS arrays per stage (not one block with run-time offsets): the compiler can then
+  // prove that an LDS-DMA load into one stage and the fragment reads of another stage do not
+  // alias, and does not make the reads wait for the loads just issued.
   __shared__ __attribute__((aligned(1024))) char lds_a0[A_STAGE_BYTES];
   __shared__ __attribute__((aligned(1024))) char lds_a1[A_STAGE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char lds_a2[A_STAGE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char lds_a3[A_STAGE_BYTES];
   __shared__ __attribute__((aligned(1024))) char lds_b0[B_STAGE_BYTES];
   __shared__ __attribute__((aligned(1024))) char lds_b1[B_STAGE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char lds_b2[B_STAGE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char lds_b3[B_STAGE_BYTES];
+  auto stage_a = [&](auto st) -> char* {
+    return st.value == 0 ? lds_a0 : st.value == 1 ? lds_a1 : st.value == 2 ? lds_a2 : lds_a3;
+  };
+  auto stage_b = [&](auto st) -> char* {
+    return st.value == 0 ? lds_b0 : st.value == 1 ? lds_b1 : st.value == 2 ? lds_b2 : lds_b3;
+  };
 
   // ---- block -> tile: patches of (32 / patch_n) row tiles x patch_n column tiles per XCD
   const int tid = threadIdx.x;
@@ -121,25 +147,25 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
   // A wavefront-wide 16-byte load writes 1 KB of contiguous LDS, lane l at byte 16*l, so the
   // LDS layouts are swizzled through the choice of the global address each lane reads.
   const int wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64;
-  // A stage: 256 rows x 128 bytes (64 k).  Load i of wave w fills rows 64w + 8i .. +7; the lane
-  // at 16-byte slot p of row r holds k-chunk p ^ ((r >> 1) & 7), which makes the 16-byte
+  // A stage: 256 rows x 64 bytes (32 k).  Load i of wave w fills rows 64w + 16i .. +15; the lane
+  // at 16-byte slot p of row r holds k-chunk p ^ ((r >> 2) & 3), which makes the 16-byte
   // fragment reads of 16 consecutive rows hit 16 different bank groups.
-  uint32_t a_goff[8];
+  uint32_t a_goff[4];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int r = wave * 64 + i * 8 + lane / 8;
-    const int chunk = (lane % 8) ^ ((r >> 1) & 7);
-    a_goff[i] = ((uint32_t)min(r, rows - 1) * (uint32_t)K + chunk * 8) * 2;
+  for (int i = 0; i < 4; ++i) {
+    const int r = wave * 64 + i * 16 + lane / 4;
+    const int chunk = (lane % 4) ^ ((r >> 2) & 3);
+    a_goff[i] = ((uint32_t)min(r, rows - 1) * (uint32_t)lda + chunk * 8) * 2;
   }
-  const char* a_gbase = (const char*)(A + (size_t)row0 * K);
-  // B stage: two parts (gate | up, or the two column halves) of 64 k-rows x 256 bytes (128
+  const char* a_gbase = (const char*)(A + (size_t)row0 * lda);
+  // B stage: two parts (gate | up, or the two column halves) of 32 k-rows x 256 bytes (128
   // columns).  Waves 0,1 fill part 0, waves 2,3 part 1; load i fills k-rows 4q .. 4q+3,
-  // q = 8*(w%2) + i.  Inside a row the four 64-byte groups are XOR-ed with (row & 3) so that
+  // q = 4*(w%2) + i.  Inside a row the four 64-byte groups are XOR-ed with (row & 3) so that
   // the transposing reads of 4 consecutive k-rows cover all banks.
   const int part = wave / 2;
   const int b_r = lane / 16;                       // k-row inside the load (= row & 3)
   const int b_slot = ((((lane % 16) >> 2) ^ b_r) << 2) | (lane & 3);   // 16-byte column slot read
-  const uint32_t b_goff = ((uint32_t)((wave % 2) * 32 + b_r) * (uint32_t)N + b_slot * 8) * 2;
+  const uint32_t b_goff = ((uint32_t)((wave % 2) * 16 + b_r) * (uint32_t)N + b_slot * 8) * 2;
   const char* b_gbase;
   if (MODE == 0)
     b_gbase = (const char*)((const uint16_t*)(part ? wt.w1[g] : wt.w0[g]) + (size_t)nt * 128);
@@ -147,30 +173,25 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
     b_gbase = (const char*)((const uint16_t*)wt.w0[g] + (size_t)nt * 256 + part * 128);
   const size_t b_row_bytes = (size_t)N * 2;
 
-  auto issue_loads = [&](auto stage, int k0) {
-    char* a_dst = (stage.value ? lds_a1 : lds_a0) + wave * 8192;
-    char* b_dst = (stage.value ? lds_b1 : lds_b0) + part * B_PART_BYTES + (wave % 2) * 8192;
-    const char* ag = a_gbase + (size_t)k0 * 2;
-    const char* bg = b_gbase + (size_t)k0 * b_row_bytes;
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-      __builtin_amdgcn_global_load_lds((gptr_t*)(ag + a_goff[i]), (lptr_t*)(a_dst + i * 1024), 16, 0, 0);
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-      __builtin_amdgcn_global_load_lds((gptr_t*)(bg + (size_t)i * 4 * b_row_bytes + b_goff),
-                                       (lptr_t*)(b_dst + i * 1024), 16, 0, 0);
+  // one wavefront-wide load (1 KB) of the A / B tile at k0 into `stage`, i = 0..3
+  auto issue_a = [&](auto stage, int k0, int i) {
+    load_to_lds_16(a_gbase + (size_t)k0 * 2 + a_goff[i], lds_offset(stage_a(stage) + wave * 4096 + i * 1024));
+  };
+  auto issue_b = [&](auto stage, int k0, int i) {
+    load_to_lds_16(b_gbase + ((size_t)k0 + 4 * i) * b_row_bytes + b_goff,
+                   lds_offset(stage_b(stage) + part * B_PART_BYTES + (wave % 2) * 4096 + i * 1024));
   };
 
   // ---- wave tiling: 2 x 2 waves, each 128 rows x 128 weight columns
   const int wm = wave / 2, wn = wave % 2;
   const int l32 = lane % 32, h = lane / 32;
   // A fragment (mi, ks): row wm*128 + mi*32 + l32, k-chunk 2*ks + h, at its swizzled slot
-  uint32_t a_addr[4][4];
+  uint32_t a_addr[4][2];
 #pragma unroll
   for (int mi = 0; mi < 4; ++mi) {
     const int r = wm * 128 + mi * 32 + l32;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) a_addr[mi][ks] = r * 128 + (((2 * ks + h) ^ ((r >> 1) & 7)) * 16);
+    for (int ks = 0; ks < 2; ++ks) a_addr[mi][ks] = r * 64 + (((2 * ks + h) ^ ((r >> 2) & 3)) * 16);
   }
   // B fragment (nj, ks): transposing read; lane s of a 16-lane group addresses 4 columns of
   // k-row s/4 and ends up with the 4 k-values of column (lane % 16) of the 16-column block
@@ -195,88 +216,113 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[mi][nj][v] = 0.f;
 
-  bf16x8 af[2][4], bfr[2][4];
-  auto load_frags = [&](auto stage, int ks, int buf) {
-    const char* sa = stage.value ? lds_a1 : lds_a0;
-    const char* sb = (stage.value ? lds_b1 : lds_b0) + ks * 16 * 256;
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi) af[buf][mi] = *(const bf16x8*)(sa + a_addr[mi][ks]);
-#pragma unroll
-    for (int nj = 0; nj < 4; ++nj) {
-      typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
-      const char* p = sb + b_addr[nj];
-      const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)p);
-      const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(p + 4 * 256));
-      bfr[buf][nj] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+  // fragment registers, double-buffered over the two 16-wide k-slices of a step
+  bf16x8 af[2][4];
+  i16x4 bl[2][4], bh[2][4];
+  // fragment read j of 12: j < 4: A rows block j; else B column block (j-4)/2, k-half (j-4)%2
+  auto read_frag = [&](auto stage, int ks, int buf, int j) {
+    typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
+    if (j < 4) {
+      af[buf][j] = *(const bf16x8*)(stage_a(stage) + a_addr[j][ks]);
+    } else {
+      const int nj = (j - 4) / 2;
+      const char* p = stage_b(stage) + ks * 16 * 256 + b_addr[nj];
+      if ((j - 4) % 2 == 0)
+        bl[buf][nj] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)p);
+      else
+        bh[buf][nj] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(p + 4 * 256));
     }
+  };
+  auto load_frags = [&](auto stage, int ks, int buf) {
+#pragma unroll
+    for (int j = 0; j < 12; ++j) read_frag(stage, ks, buf, j);
   };
   auto mfma16 = [&](int buf) {
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
-      for (int nj = 0; nj < 4; ++nj)
-        acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][mi], bfr[buf][nj],
-                                                             acc[mi][nj], 0, 0, 0);
+      for (int nj = 0; nj < 4; ++nj) {
+        const bf16x8 b = __builtin_bit_cast(
+            bf16x8, __builtin_shufflevector(bl[buf][nj], bh[buf][nj], 0, 1, 2, 3, 4, 5, 6, 7));
+        acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][mi], b, acc[mi][nj], 0, 0, 0);
+      }
   };
 
-  // Software pipeline.  Step kt computes from stage kt&1.  Once every wave has passed the
-  // barrier that ends the reads of a stage, the loads of the tile two steps ahead are issued
-  // into it; they have a whole step to land before the barrier that precedes their use.
-  // Loads past the end re-read the last tile (k clamped) into a stage nobody reads again, so
+  // Software pipeline over NS = 4 stages of 32 k.  Step kt computes from stage kt % 4 in two
+  // halves of 16 MFMAs per wave.  Its single barrier sits between the halves: by then every
+  // wave holds the last fragments of stage kt % 4 in registers, so that stage is free and tile
+  // kt+4 is requested into it -- the A part in the second half of step kt, the B part in the
+  // first half of step kt+1, four wavefront-wide loads per 16 MFMAs, so the address unit sees
+  // an even stream.  A tile is needed three steps after it was requested.  At the barrier of
+  // step kt the 16 most recent loads (tiles kt+2, kt+3) may still be in flight.
+  // Loads past the end re-read the last tile (k clamped) into stages nobody reads again, so
   // the loop body has no branches.
-  const int KT = K / BK;   // even: K is a multiple of 128
+  const int KT = K / BK;   // a multiple of 4: K is a multiple of 128
   const int k_last = K - BK;
+  auto kclamp = [&](int kt) { return min(kt * BK, k_last); };
   constexpr std::integral_constant<int, 0> st0{};
   constexpr std::integral_constant<int, 1> st1{};
-  auto step = [&](auto cur, auto nxt, int k2) {
-    load_frags(cur, 1, 1);
+  constexpr std::integral_constant<int, 2> st2{};
+  constexpr std::integral_constant<int, 3> st3{};
+  // cur: stage of step kt; nxt: stage of step kt+1; prv: stage of step kt-1 (receives B of tile kt+3)
+  auto step = [&](auto cur, auto nxt, auto prv, int kt) {
+    const int k3 = kclamp(kt + 3), k4 = kclamp(kt + 4);
+    // first half: B part of tile kt+3, fragments of k-slice 1, MFMAs of k-slice 0
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      issue_b(prv, k3, q);
+#pragma unroll
+      for (int j = 3 * q; j < 3 * q + 3; ++j) read_frag(cur, 1, 1, j);
+    }
     mfma16(0);
 #pragma unroll
-    for (int i = 0; i < 12; ++i) {
+    for (int i = 0; i < 16; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
+      if (i < 12) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);       // 1 LDS read
     }
     __builtin_amdgcn_sched_barrier(0);
-    load_frags(cur, 2, 0);
-    mfma16(1);
-#pragma unroll
-    for (int i = 0; i < 12; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    load_frags(cur, 3, 1);
-    mfma16(0);
-#pragma unroll
-    for (int i = 0; i < 12; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    // all reads of stage `cur` are done and the next tile has landed in the other stage
-    __builtin_amdgcn_s_waitcnt(0);
+    // tile kt+1 has landed (this wave's share; the 16 newer loads may be in flight) and all
+    // fragment reads of stage `cur` are complete
+    __builtin_amdgcn_s_waitcnt(0x4070);   // vmcnt(16) lgkmcnt(0)
     __syncthreads();
-    issue_loads(cur, k2);
-    load_frags(nxt, 0, 0);
+    // second half: A part of tile kt+4 into the stage just freed, first fragments of step kt+1
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      issue_a(cur, k4, q);
+#pragma unroll
+      for (int j = 3 * q; j < 3 * q + 3; ++j) read_frag(nxt, 0, 0, j);
+    }
     mfma16(1);
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // 1 global->LDS load
       if (i < 12) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
   };
-  issue_loads(st0, 0);
-  issue_loads(st1, min(BK, k_last));
-  __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): both tiles have landed
+  auto issue_tile = [&](auto stage, int k0, bool with_b) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) issue_a(stage, k0, q);
+    if (with_b) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) issue_b(stage, k0, q);
+    }
+  };
+  issue_tile(st0, kclamp(0), true);
+  issue_tile(st1, kclamp(1), true);
+  issue_tile(st2, kclamp(2), true);
+  issue_tile(st3, kclamp(3), false);
+  __builtin_amdgcn_s_waitcnt(0x4f74);   // vmcnt(20): tile 0 has landed
   __syncthreads();
   load_frags(st0, 0, 0);
-  for (int kt = 0; kt < KT; kt += 2) {
-    step(st0, st1, min((kt + 2) * BK, k_last));
-    step(st1, st0, min((kt + 3) * BK, k_last));
+  for (int kt = 0; kt < KT; kt += 4) {
+    step(st0, st1, st3, kt);
+    step(st1, st2, st0, kt + 1);
+    step(st2, st3, st1, kt + 2);
+    step(st3, st0, st2, kt + 3);
   }
   __builtin_amdgcn_s_waitcnt(0);   // the clamped trailing loads must land before the block ends
+  __syncthreads();
 
   // ---- epilogue: lane holds column l32 of each 32x32 tile, rows 8*(v/4) + 4*(lane/32) + v%4
   const int rsub = (lane / 32) * 4;
@@ -292,7 +338,7 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
           const int r = wm * 128 + mi * 32 + 8 * (v / 4) + rsub + (v % 4);
           if (r < rows) {
             const float h = silu(acc[mi][nj][v]) * acc[mi][nj + 2][v];
-            H[(size_t)(row0 + r) * N + col] = (uint16_t)bf16_rne(h);
+            H[(size_t)(row0 + r) * ldo + col] = (uint16_t)bf16_rne(h);
           }
         }
       }
@@ -307,9 +353,9 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
           const int r = wm * 128 + mi * 32 + 8 * (v / 4) + rsub + (v % 4);
           if (r < rows) {
             if (OUT_BF16)
-              ((uint16_t*)out)[(size_t)(row0 + r) * N + col] = (uint16_t)bf16_rne(acc[mi][nj][v]);
+              ((uint16_t*)out)[(size_t)(row0 + r) * ldo + col] = (uint16_t)bf16_rne(acc[mi][nj][v]);
             else
-              ((float*)out)[(size_t)(row0 + r) * N + col] = acc[mi][nj][v];
+              ((float*)out)[(size_t)(row0 + r) * ldo + col] = acc[mi][nj][v];
           }
         }
       }
@@ -319,8 +365,8 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
 int max_tiles_for(int R_cap, int ng) { return R_cap / BM + ng + 1; }
 
 template <int MODE, bool OUT_BF16>
-hipError_t launch_gemm(const void* A, const int4* sched, int K, int N, int n_tiles_n, int max_tiles,
-                       const WeightTable& wt, void* out, hipStream_t s) {
+hipError_t launch_gemm(const void* A, int lda, const int4* sched, int K, int N, int n_tiles_n,
+                       int max_tiles, const WeightTable& wt, void* out, int ldo, hipStream_t s) {
   const int patch_n = n_tiles_n % 4 == 0 ? 4 : (n_tiles_n % 2 == 0 ? 2 : 1);
   const int patch_m = 32 / patch_n;
   const int patches_m = (max_tiles + patch_m - 1) / patch_m;
@@ -328,7 +374,7 @@ hipError_t launch_gemm(const void* A, const int4* sched, int K, int N, int n_til
   const int patch_rounds = (patches + XCDS - 1) / XCDS;
   const unsigned blocks = (unsigned)patch_rounds * XCDS * 32;
   hipLaunchKernelGGL((grouped_gemm_kernel<MODE, OUT_BF16>), dim3(blocks), dim3(THREADS), 0,
-                     s, (const uint16_t*)A, sched, K, N, n_tiles_n, patch_n, wt, out);
+                     s, (const uint16_t*)A, lda, sched, K, N, n_tiles_n, patch_n, wt, out, ldo);
   return hipGetLastError();
 }
 
@@ -399,13 +445,13 @@ extern "C" int32_t feplb_grouped_ffn(const void* Xp, const int32_t* offsets, int
     FEPLB_LAUNCH_CHECK("ffn_schedule_kernel");
   }
   if (do_up) {
-    FEPLB_HIP((launch_gemm<0, true>(Xp, (const int4*)ws, d, f, f / 128, max_tiles, up_tab, H, s)));
+    FEPLB_HIP((launch_gemm<0, true>(Xp, d, (const int4*)ws, d, f, f / 128, max_tiles, up_tab, H, f, s)));
   }
   if (do_down) {
     if (yp_dtype == FEPLB_BF16)
-      FEPLB_HIP((launch_gemm<1, true>(H, (const int4*)ws, f, d, d / 256, max_tiles, down_tab, Yp, s)));
+      FEPLB_HIP((launch_gemm<1, true>(H, f, (const int4*)ws, f, d, d / 256, max_tiles, down_tab, Yp, d, s)));
     else
-      FEPLB_HIP((launch_gemm<1, false>(H, (const int4*)ws, f, d, d / 256, max_tiles, down_tab, Yp, s)));
+      FEPLB_HIP((launch_gemm<1, false>(H, f, (const int4*)ws, f, d, d / 256, max_tiles, down_tab, Yp, d, s)));
   }
   return FEPLB_OK;
 }
