@@ -163,7 +163,7 @@ def main():
     ap.add_argument("--source", default="device", choices=["device", "pinned"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all", action="store_true", help="also time the other four workloads (reported under all_workloads)")
-    ap.add_argument("--cpu-tokens", type=int, default=512)
+    ap.add_argument("--cpu-tokens", type=int, default=8192)
     a = ap.parse_args()
     if a.gpus != 1:
         log("bench.py: this build is a single-GPU hot path (one EP rank's share); run it with --gpus 1")

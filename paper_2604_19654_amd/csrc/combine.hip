@@ -13,6 +13,7 @@ constexpr int BLOCK = WAVES * 64;
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ uint32_t bf16_rne(float x) {
   uint32_t u = __float_as_uint(x);
@@ -24,11 +25,20 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
   return bf16_rne(lo) | (bf16_rne(hi) << 16);
 }
 
-template <bool YP_BF16>
+// One wavefront per token.  The token's local slots are compacted into a wave-uniform bit mask,
+// walked in ascending j (the summation order is fixed).  A lane owns 16 bytes of the SOURCE row
+// per step (4 fp32 or 8 bf16 values), so every load instruction of the wavefront covers 1 KB of
+// contiguous memory; per slot, UNROLL such loads are issued before the accumulators are touched,
+// so that a token with a single local slot (the common case after top-k over many ranks) still
+// has UNROLL independent loads in flight per lane.  Rows are read once and Y is written once:
+// both are marked non-temporal.
+template <bool YP_BF16, int UNROLL>
 __global__ __launch_bounds__(BLOCK) void combine_kernel(const void* __restrict__ Yp,
                                                         const int* __restrict__ inv,
                                                         const float* __restrict__ w, int T, int k,
-                                                        int nvec, u32x4* __restrict__ Y) {
+                                                        int d, void* __restrict__ Y) {
+  constexpr int PER = YP_BF16 ? 8 : 4;   // values per lane and load
+  const int nchunk = d / PER;
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
   const long long t = (long long)blockIdx.x * WAVES + wave;
   if (t >= T) return;
@@ -38,42 +48,63 @@ __global__ __launch_bounds__(BLOCK) void combine_kernel(const void* __restrict__
     my_row = inv[t * k + lane];
     my_w = w[t * k + lane];
   }
-  u32x4* out = Y + t * nvec;
-  // the loop bound is uniform so that every lane takes part in the broadcasts
-  for (int v0 = 0; v0 < nvec; v0 += 64) {
-    const int v = v0 + lane;
-    const bool live = v < nvec;
-    float acc[8];
+  const unsigned long long local = __ballot(my_row >= 0);
+  for (int c0 = 0; c0 < nchunk; c0 += 64 * UNROLL) {
+    float acc[UNROLL][PER];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) acc[i] = 0.f;
-    for (int j = 0; j < k; ++j) {
-      const int r = __shfl(my_row, j, 64);
-      if (r < 0) continue;  // uniform across the wave
-      const float wj = __shfl(my_w, j, 64);
-      if (!live) continue;
+    for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+      for (int i = 0; i < PER; ++i) acc[u][i] = 0.f;
+    for (unsigned long long m = local; m; m &= m - 1) {
+      const int j = __builtin_ctzll(m);
+      const int r = __builtin_amdgcn_readlane(my_row, j);
+      const float wj = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(my_w), j));
       if (YP_BF16) {
-        const u32x4 p = ((const u32x4*)Yp)[(long long)r * nvec + v];
+        const u32x4* row = (const u32x4*)Yp + (long long)r * nchunk;
+        u32x4 p[UNROLL];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          acc[2 * i] = fmaf(wj, __uint_as_float(p[i] << 16), acc[2 * i]);
-          acc[2 * i + 1] = fmaf(wj, __uint_as_float(p[i] & 0xffff0000u), acc[2 * i + 1]);
+        for (int u = 0; u < UNROLL; ++u) {
+          const int c = c0 + u * 64 + lane;
+          p[u] = c < nchunk ? __builtin_nontemporal_load(row + c) : u32x4{0, 0, 0, 0};
         }
-      } else {
-        const f32x4* row = (const f32x4*)Yp + ((long long)r * nvec + v) * 2;
-        const f32x4 p0 = row[0], p1 = row[1];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          acc[i] = fmaf(wj, p0[i], acc[i]);
-          acc[4 + i] = fmaf(wj, p1[i], acc[4 + i]);
+        for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            acc[u][2 * i] = fmaf(wj, __uint_as_float(p[u][i] << 16), acc[u][2 * i]);
+            acc[u][2 * i + 1] = fmaf(wj, __uint_as_float(p[u][i] & 0xffff0000u), acc[u][2 * i + 1]);
+          }
+      } else {
+        const f32x4* row = (const f32x4*)Yp + (long long)r * nchunk;
+        f32x4 p[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+          const int c = c0 + u * 64 + lane;
+          p[u] = c < nchunk ? __builtin_nontemporal_load(row + c) : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) acc[u][i] = fmaf(wj, p[u][i], acc[u][i]);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const int c = c0 + u * 64 + lane;
+      if (c < nchunk) {
+        if (YP_BF16) {
+          u32x4 o;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) o[i] = pack2(acc[u][2 * i], acc[u][2 * i + 1]);
+          __builtin_nontemporal_store(o, (u32x4*)Y + t * nchunk + c);
+        } else {
+          u32x2 o;
+          o[0] = pack2(acc[u][0], acc[u][1]);
+          o[1] = pack2(acc[u][2], acc[u][3]);
+          __builtin_nontemporal_store(o, (u32x2*)Y + t * nchunk + c);
         }
       }
     }
-    u32x4 o;
-    o[0] = pack2(acc[0], acc[1]);
-    o[1] = pack2(acc[2], acc[3]);
-    o[2] = pack2(acc[4], acc[5]);
-    o[3] = pack2(acc[6], acc[7]);
-    if (live) out[v] = o;
   }
 }
 
@@ -95,11 +126,11 @@ extern "C" int32_t feplb_unpermute_combine(const void* Yp, int32_t yp_dtype, con
   hipStream_t s = (hipStream_t)stream;
   const int blocks = (T + WAVES - 1) / WAVES;
   if (yp_dtype == FEPLB_BF16)
-    hipLaunchKernelGGL(combine_kernel<true>, dim3(blocks), dim3(BLOCK), 0, s, Yp, inv, topk_w, T,
-                       k, d / 8, (u32x4*)Y);
+    hipLaunchKernelGGL((combine_kernel<true, 6>), dim3(blocks), dim3(BLOCK), 0, s, Yp, inv,
+                       topk_w, T, k, d, Y);
   else
-    hipLaunchKernelGGL(combine_kernel<false>, dim3(blocks), dim3(BLOCK), 0, s, Yp, inv, topk_w, T,
-                       k, d / 8, (u32x4*)Y);
+    hipLaunchKernelGGL((combine_kernel<false, 12>), dim3(blocks), dim3(BLOCK), 0, s, Yp, inv,
+                       topk_w, T, k, d, Y);
   FEPLB_LAUNCH_CHECK("combine_kernel");
   return FEPLB_OK;
 }

@@ -190,6 +190,7 @@ __global__ __launch_bounds__(BLOCK) void assign_rows_kernel(
   }
 }
 
+template <int UNROLL>
 __global__ __launch_bounds__(BLOCK) void gather_rows_kernel(const u32x4* __restrict__ X,
                                                             const int* __restrict__ row_src,
                                                             const int* __restrict__ offsets, int G,
@@ -202,18 +203,21 @@ __global__ __launch_bounds__(BLOCK) void gather_rows_kernel(const u32x4* __restr
   const long long t = row_src[r] / k;
   const u32x4* src = X + t * nvec;
   u32x4* dst = Xp + r * nvec;
-  int v = lane;
-  for (; v + 192 < nvec; v += 256) {
-    const u32x4 a = __builtin_nontemporal_load(src + v);
-    const u32x4 b = __builtin_nontemporal_load(src + v + 64);
-    const u32x4 c = __builtin_nontemporal_load(src + v + 128);
-    const u32x4 d = __builtin_nontemporal_load(src + v + 192);
-    dst[v] = a;
-    dst[v + 64] = b;
-    dst[v + 128] = c;
-    dst[v + 192] = d;
+  for (int v0 = 0; v0 < nvec; v0 += 64 * UNROLL) {
+    u32x4 p[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const int v = v0 + u * 64 + lane;
+      if (v < nvec) p[u] = __builtin_nontemporal_load(src + v);
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const int v = v0 + u * 64 + lane;
+      if (v < nvec) {
+        dst[v] = p[u];
+      }
+    }
   }
-  for (; v < nvec; v += 64) dst[v] = __builtin_nontemporal_load(src + v);
 }
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -308,7 +312,7 @@ extern "C" int32_t feplb_permute(const int32_t* topk_ids, int32_t T, int32_t k, 
   }
   if (X && Xp && R_cap > 0 && d > 0) {
     const int blocks = (R_cap + WAVES - 1) / WAVES;
-    hipLaunchKernelGGL(gather_rows_kernel, dim3(blocks), dim3(BLOCK), 0, s, (const u32x4*)X,
+    hipLaunchKernelGGL((gather_rows_kernel<4>), dim3(blocks), dim3(BLOCK), 0, s, (const u32x4*)X,
                        row_src, offsets, G, k, d / 8, R_cap, (u32x4*)Xp);
     FEPLB_LAUNCH_CHECK("gather_rows_kernel");
   }

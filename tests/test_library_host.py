@@ -52,7 +52,7 @@ def test_argument_validation_happens_before_any_device_work():
     rc = L.feplb_grouped_ffn(None, None, 0, 1, 128, 256, 128, None, None, None, None, None, 0, 0, None, 0, None)
     assert rc == -1
     assert fe.feplb_permute_workspace_bytes(1024, 8, 128, 20) > 0
-    assert fe.feplb_grouped_ffn_workspace_bytes(4096, 20) >= (4096 // 128 + 20) * 16
+    assert fe.feplb_grouped_ffn_workspace_bytes(4096, 20) >= (4096 // 256 + 20) * 16   # one entry per 256-row tile
 
 
 def as_tuples(moves):
