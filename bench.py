@@ -24,6 +24,10 @@ if ROOT not in sys.path:
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 (no sparsity)
 HBM_PEAK_GBPS = 8000.0
+# HBM bytes per launch of the gate/up GEMM (read + written), measured with rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE and calibrated against the row-copy kernel of the same run; see
+# profiles/hbm_traffic_C4_pmc.md.  Only for the workload it was measured on.
+MEASURED_TRAFFIC_BYTES = {"C4": 5.317e9 + 0.270e9}
 METRIC = "grouped-FFN TFLOP/s & % bf16 MFMA peak per rank share; permute/combine GB/s"
 
 
@@ -206,7 +210,10 @@ def main():
                    "yp_dtype": "f32", "staging_source": a.source if a.workload == "C4" else None},
         "roofline": {"kernel": "grouped_gemm_kernel<0,true> (gate/up GEMM + SwiGLU)", "bound": "mfma",
                      "achieved": up_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": up_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "frac": up_tflops / MFMA_BF16_PEAK_TFLOPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(a.workload),
+                     "traffic_unit": "bytes per launch (HBM read + write, rocprofv3 --pmc, profiles/hbm_traffic_C4_pmc.md)",
+                     "algorithmic_bytes_per_launch": _gate_up_min_bytes(res),
                      "launches_per_step": res["gate_up_launches_per_step"],
                      "avg_launch_ms": res["gate_up_ms_per_launch"],
                      "flops_per_launch": 4.0 * res["d"] * res["f"] * res["R"] / res["gate_up_launches_per_step"]},
@@ -217,6 +224,14 @@ def main():
     if others:
         out["all_workloads"] = others
     print(json.dumps(out), flush=True)
+
+
+def _gate_up_min_bytes(res):
+    """Unique operand bytes of the gate/up GEMM per launch: both weight matrices of every
+    non-empty group once, Xp once, H written once (averaged over the launches of a step)."""
+    groups = res.get("nonempty_groups", res["groups"])
+    total = groups * 2 * res["d"] * res["f"] * 2 + res["R"] * res["d"] * 2 + res["R"] * res["f"] * 2
+    return total / res["gate_up_launches_per_step"]
 
 
 def _device_info(prop):
