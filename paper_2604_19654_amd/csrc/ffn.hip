@@ -70,32 +70,45 @@ struct WeightTable {
 };
 
 // ws layout: int4 header {n_tiles,0,0,0}, then int4 {group, row0, rows, 0} per tile
-__global__ __launch_bounds__(FEPLB_MAX_GROUPS) void ffn_schedule_kernel(
+constexpr int SCHED_THREADS = 256;
+__global__ __launch_bounds__(SCHED_THREADS) void ffn_schedule_kernel(
     const int* __restrict__ offsets, int g_begin, int g_end, int R_cap, int max_tiles,
     int4* __restrict__ ws) {
-  __shared__ int scan[FEPLB_MAX_GROUPS];
+  // inclusive scan of the groups' tile counts, then every thread places tiles by binary search
+  __shared__ int scan[FEPLB_MAX_GROUPS], lo_s[FEPLB_MAX_GROUPS], hi_s[FEPLB_MAX_GROUPS];
   const int i = threadIdx.x;
-  const int g = g_begin + i;
-  int lo = 0, hi = 0, mt = 0;
-  if (g < g_end) {
-    lo = min(offsets[g], R_cap);
-    hi = min(offsets[g + 1], R_cap);
-    mt = hi > lo ? (hi - lo + BM - 1) / BM : 0;
+  if (i < FEPLB_MAX_GROUPS) {
+    const int g = g_begin + i;
+    int lo = 0, hi = 0, mt = 0;
+    if (g < g_end) {
+      lo = min(offsets[g], R_cap);
+      hi = min(offsets[g + 1], R_cap);
+      mt = hi > lo ? (hi - lo + BM - 1) / BM : 0;
+    }
+    scan[i] = mt;
+    lo_s[i] = lo;
+    hi_s[i] = hi;
   }
-  scan[i] = mt;
   __syncthreads();
   for (int d = 1; d < FEPLB_MAX_GROUPS; d <<= 1) {
-    const int v = i >= d ? scan[i - d] : 0;
+    int v = 0;
+    if (i < FEPLB_MAX_GROUPS && i >= d) v = scan[i - d];
     __syncthreads();
-    scan[i] += v;
+    if (i < FEPLB_MAX_GROUPS) scan[i] += v;
     __syncthreads();
   }
-  int first = scan[i] - mt;
-  for (int m = 0; m < mt; ++m) {
-    const int idx = first + m;
-    if (idx < max_tiles) ws[1 + idx] = make_int4(g, lo + m * BM, min(BM, hi - lo - m * BM), 0);
+  const int total = min(scan[FEPLB_MAX_GROUPS - 1], max_tiles);
+  for (int t = i; t < total; t += SCHED_THREADS) {
+    int a = 0, b = FEPLB_MAX_GROUPS - 1;   // first group whose inclusive count exceeds t
+    while (a < b) {
+      const int m = (a + b) / 2;
+      if (scan[m] > t) b = m; else a = m + 1;
+    }
+    const int first = a ? scan[a - 1] : 0;
+    const int row0 = lo_s[a] + (t - first) * BM;
+    ws[1 + t] = make_int4(g_begin + a, row0, min(BM, hi_s[a] - row0), 0);
   }
-  if (i == FEPLB_MAX_GROUPS - 1) ws[0] = make_int4(min(scan[i], max_tiles), 0, 0, 0);
+  if (i == 0) ws[0] = make_int4(total, 0, 0, 0);
 }
 
 __device__ __forceinline__ uint32_t bf16_rne(float x) {
@@ -440,7 +453,7 @@ extern "C" int32_t feplb_grouped_ffn(const void* Xp, const int32_t* offsets, int
   FEPLB_REQUIRE(feplb::aligned16(ws), FEPLB_EALIGN, "grouped_ffn: workspace not 16-byte aligned");
   hipStream_t s = (hipStream_t)stream;
   if (phases & FEPLB_FFN_SCHEDULE) {
-    hipLaunchKernelGGL(ffn_schedule_kernel, dim3(1), dim3(FEPLB_MAX_GROUPS), 0, s, offsets,
+    hipLaunchKernelGGL(ffn_schedule_kernel, dim3(1), dim3(SCHED_THREADS), 0, s, offsets,
                        g_begin, g_end, R_cap, max_tiles, (int4*)ws);
     FEPLB_LAUNCH_CHECK("ffn_schedule_kernel");
   }
