@@ -54,11 +54,18 @@ constexpr int XCDS = 8;
 // inline assembly so that the loads' completion is tracked by the explicit s_waitcnt vmcnt(n)
 // of the pipeline below: the compiler's own tracking would wait for ALL outstanding loads
 // before any LDS read in a loop, i.e. also for the tiles requested for later steps.
-__device__ __forceinline__ void load_to_lds_16(const void* gptr, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
+// The address is a wave-uniform base (scalar register pair) plus a 32-bit per-lane byte offset.
+__device__ __forceinline__ void load_to_lds_16(const char* base, uint32_t lane_off, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
                :
-               : "v"(gptr), "s"(lds_base)
+               : "v"(lane_off), "s"(base), "s"(lds_base)
                : "memory", "m0");
+}
+__device__ __forceinline__ const char* wave_uniform(const void* p) {
+  const uint64_t v = (uint64_t)(uintptr_t)p;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return (const char*)(uintptr_t)(((uint64_t)hi << 32) | lo);
 }
 __device__ __forceinline__ uint32_t lds_offset(const void* p) {
   return (uint32_t)(uintptr_t)p;   // low half of a generic LDS address is the LDS byte offset
@@ -170,7 +177,7 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
     const int chunk = (lane % 4) ^ ((r >> 2) & 3);
     a_goff[i] = ((uint32_t)min(r, rows - 1) * (uint32_t)lda + chunk * 8) * 2;
   }
-  const char* a_gbase = (const char*)(A + (size_t)row0 * lda);
+  const char* a_gbase = wave_uniform(A + (size_t)row0 * lda);
   // B stage: two parts (gate | up, or the two column halves) of 32 k-rows x 256 bytes (128
   // columns).  Waves 0,1 fill part 0, waves 2,3 part 1; load i fills k-rows 4q .. 4q+3,
   // q = 4*(w%2) + i.  Inside a row the four 64-byte groups are XOR-ed with (row & 3) so that
@@ -181,17 +188,17 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
   const uint32_t b_goff = ((uint32_t)((wave % 2) * 16 + b_r) * (uint32_t)N + b_slot * 8) * 2;
   const char* b_gbase;
   if (MODE == 0)
-    b_gbase = (const char*)((const uint16_t*)(part ? wt.w1[g] : wt.w0[g]) + (size_t)nt * 128);
+    b_gbase = wave_uniform((const uint16_t*)(part ? wt.w1[g] : wt.w0[g]) + (size_t)nt * 128);
   else
-    b_gbase = (const char*)((const uint16_t*)wt.w0[g] + (size_t)nt * 256 + part * 128);
+    b_gbase = wave_uniform((const uint16_t*)wt.w0[g] + (size_t)nt * 256 + part * 128);
   const size_t b_row_bytes = (size_t)N * 2;
 
   // one wavefront-wide load (1 KB) of the A / B tile at k0 into `stage`, i = 0..3
   auto issue_a = [&](auto stage, int k0, int i) {
-    load_to_lds_16(a_gbase + (size_t)k0 * 2 + a_goff[i], lds_offset(stage_a(stage) + wave * 4096 + i * 1024));
+    load_to_lds_16(a_gbase + (size_t)k0 * 2, a_goff[i], lds_offset(stage_a(stage) + wave * 4096 + i * 1024));
   };
   auto issue_b = [&](auto stage, int k0, int i) {
-    load_to_lds_16(b_gbase + ((size_t)k0 + 4 * i) * b_row_bytes + b_goff,
+    load_to_lds_16(b_gbase + ((size_t)k0 + 4 * i) * b_row_bytes, b_goff,
                    lds_offset(stage_b(stage) + part * B_PART_BYTES + (wave % 2) * 4096 + i * 1024));
   };
 
