@@ -41,9 +41,11 @@ typedef __attribute__((address_space(3))) void lptr_t;
 constexpr int BM = 256;      // rows per tile
 constexpr int BNW = 256;     // weight columns per tile
 constexpr int BK = 32;       // k per step
-constexpr int NS = 4;        // LDS stages
+constexpr int NSA = 6;       // LDS stages of the A operand
+constexpr int NSB = 4;       // LDS stages of the B operand
 constexpr int THREADS = 256;
-// LDS: NS A stages and NS B stages of 16 KB each; a B stage is two parts of 32 k-rows x 256 bytes.
+// LDS: NSA A stages and NSB B stages of 16 KB each (160 KB, all of a CU's LDS); a B stage is two
+// parts of 32 k-rows x 256 bytes.
 constexpr int A_STAGE_BYTES = BM * BK * 2;
 constexpr int B_PART_BYTES = BK * 128 * 2;
 constexpr int B_STAGE_BYTES = 2 * B_PART_BYTES;
@@ -138,12 +140,15 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
   __shared__ __attribute__((aligned(1024))) char lds_a1[A_STAGE_BYTES];
   __shared__ __attribute__((aligned(1024))) char lds_a2[A_STAGE_BYTES];
   __shared__ __attribute__((aligned(1024))) char lds_a3[A_STAGE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char lds_a4[A_STAGE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char lds_a5[A_STAGE_BYTES];
   __shared__ __attribute__((aligned(1024))) char lds_b0[B_STAGE_BYTES];
   __shared__ __attribute__((aligned(1024))) char lds_b1[B_STAGE_BYTES];
   __shared__ __attribute__((aligned(1024))) char lds_b2[B_STAGE_BYTES];
   __shared__ __attribute__((aligned(1024))) char lds_b3[B_STAGE_BYTES];
   auto stage_a = [&](auto st) -> char* {
-    return st.value == 0 ? lds_a0 : st.value == 1 ? lds_a1 : st.value == 2 ? lds_a2 : lds_a3;
+    return st.value == 0 ? lds_a0 : st.value == 1 ? lds_a1 : st.value == 2 ? lds_a2
+         : st.value == 3 ? lds_a3 : st.value == 4 ? lds_a4 : lds_a5;
   };
   auto stage_b = [&](auto st) -> char* {
     return st.value == 0 ? lds_b0 : st.value == 1 ? lds_b1 : st.value == 2 ? lds_b2 : lds_b3;
@@ -240,22 +245,22 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
   bf16x8 af[2][4];
   i16x4 bl[2][4], bh[2][4];
   // fragment read j of 12: j < 4: A rows block j; else B column block (j-4)/2, k-half (j-4)%2
-  auto read_frag = [&](auto stage, int ks, int buf, int j) {
+  auto read_frag = [&](auto sa, auto sb, int ks, int buf, int j) {
     typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
     if (j < 4) {
-      af[buf][j] = *(const bf16x8*)(stage_a(stage) + a_addr[j][ks]);
+      af[buf][j] = *(const bf16x8*)(stage_a(sa) + a_addr[j][ks]);
     } else {
       const int nj = (j - 4) / 2;
-      const char* p = stage_b(stage) + ks * 16 * 256 + b_addr[nj];
+      const char* p = stage_b(sb) + ks * 16 * 256 + b_addr[nj];
       if ((j - 4) % 2 == 0)
         bl[buf][nj] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)p);
       else
         bh[buf][nj] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(p + 4 * 256));
     }
   };
-  auto load_frags = [&](auto stage, int ks, int buf) {
+  auto load_frags = [&](auto sa, auto sb, int ks, int buf) {
 #pragma unroll
-    for (int j = 0; j < 12; ++j) read_frag(stage, ks, buf, j);
+    for (int j = 0; j < 12; ++j) read_frag(sa, sb, ks, buf, j);
   };
   auto mfma16 = [&](int buf) {
 #pragma unroll
@@ -268,31 +273,44 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
       }
   };
 
-  // Software pipeline over NS = 4 stages of 32 k.  Step kt computes from stage kt % 4 in two
-  // halves of 16 MFMAs per wave.  Its single barrier sits between the halves: by then every
-  // wave holds the last fragments of stage kt % 4 in registers, so that stage is free and tile
-  // kt+4 is requested into it -- the A part in the second half of step kt, the B part in the
-  // first half of step kt+1, four wavefront-wide loads per 16 MFMAs, so the address unit sees
-  // an even stream.  A tile is needed three steps after it was requested.  At the barrier of
-  // step kt the 16 most recent loads (tiles kt+2, kt+3) may still be in flight.
+  // Software pipeline over 32-wide k tiles.  Step kt computes tile kt in two halves of 16 MFMAs
+  // per wave, from A stage kt % 6 and B stage kt % 4.  Its single barrier sits between the
+  // halves: by then every wave holds the last fragments of tile kt in registers and its stages
+  // are free.
+  //   B: tile kt+3 is requested in the first half of step kt (into the stage freed by step kt-1).
+  //   A: a row of a 32-wide tile is 64 bytes, half a 128-byte memory line, and a line fetched
+  //      for one tile would be evicted from the vector cache before the next tile asks for its
+  //      other half.  So A tiles are requested in pairs (t, t+1), t even, by back-to-back loads
+  //      of the two halves of the same lines, which the cache merges into one fetch: row
+  //      blocks 0,1 of tiles (kt+5, kt+6) in the second half of an odd step kt, row blocks 2,3
+  //      of the same pair in the second half of the next (even) step.  Six A stages hold the
+  //      four tiles ahead of the one being computed plus the pair in flight.
+  // Every half step thus issues four wavefront-wide loads per 16 MFMAs, an even stream for the
+  // address unit.  At the barrier of step kt the 16 most recent loads may still be in flight;
+  // the older ones include all of tile kt+1.
   // Loads past the end re-read the last tile (k clamped) into stages nobody reads again, so
-  // the loop body has no branches.
+  // the loop body has no branches except the exits after every fourth step.
   const int KT = K / BK;   // a multiple of 4: K is a multiple of 128
   const int k_last = K - BK;
   auto kclamp = [&](int kt) { return min(kt * BK, k_last); };
-  constexpr std::integral_constant<int, 0> st0{};
-  constexpr std::integral_constant<int, 1> st1{};
-  constexpr std::integral_constant<int, 2> st2{};
-  constexpr std::integral_constant<int, 3> st3{};
-  // cur: stage of step kt; nxt: stage of step kt+1; prv: stage of step kt-1 (receives B of tile kt+3)
-  auto step = [&](auto cur, auto nxt, auto prv, int kt) {
-    const int k3 = kclamp(kt + 3), k4 = kclamp(kt + 4);
+  auto step = [&](auto sc, int kt) {
+    constexpr int s = decltype(sc)::value;                       // kt mod 12
+    constexpr std::integral_constant<int, s % NSA> a_cur{};
+    constexpr std::integral_constant<int, (s + 1) % NSA> a_nxt{};
+    constexpr std::integral_constant<int, s % NSB> b_cur{};
+    constexpr std::integral_constant<int, (s + 1) % NSB> b_nxt{};
+    constexpr std::integral_constant<int, (s + 3) % NSB> b_req{};
+    constexpr int pair = (s % 2) ? 5 : 4;                        // first tile of the A pair, relative to kt
+    constexpr int q0 = (s % 2) ? 0 : 2;                          // its row blocks requested in this step
+    constexpr std::integral_constant<int, (s + pair) % NSA> a_req0{};
+    constexpr std::integral_constant<int, (s + pair + 1) % NSA> a_req1{};
+    const int kb = kclamp(kt + 3), ka0 = kclamp(kt + pair), ka1 = kclamp(kt + pair + 1);
     // first half: B part of tile kt+3, fragments of k-slice 1, MFMAs of k-slice 0
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      issue_b(prv, k3, q);
+      issue_b(b_req, kb, q);
 #pragma unroll
-      for (int j = 3 * q; j < 3 * q + 3; ++j) read_frag(cur, 1, 1, j);
+      for (int j = 3 * q; j < 3 * q + 3; ++j) read_frag(a_cur, b_cur, 1, 1, j);
     }
     mfma16(0);
 #pragma unroll
@@ -302,15 +320,18 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
     }
     __builtin_amdgcn_sched_barrier(0);
     // tile kt+1 has landed (this wave's share; the 16 newer loads may be in flight) and all
-    // fragment reads of stage `cur` are complete
+    // fragment reads of tile kt are complete
     __builtin_amdgcn_s_waitcnt(0x4070);   // vmcnt(16) lgkmcnt(0)
     __syncthreads();
-    // second half: A part of tile kt+4 into the stage just freed, first fragments of step kt+1
+    // second half: two row blocks of an A pair, first fragments of step kt+1
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      issue_a(cur, k4, q);
+      if (q % 2 == 0)
+        issue_a(a_req0, ka0, q0 + q / 2);
+      else
+        issue_a(a_req1, ka1, q0 + q / 2);
 #pragma unroll
-      for (int j = 3 * q; j < 3 * q + 3; ++j) read_frag(nxt, 0, 0, j);
+      for (int j = 3 * q; j < 3 * q + 3; ++j) read_frag(a_nxt, b_nxt, 0, 0, j);
     }
     mfma16(1);
 #pragma unroll
@@ -320,26 +341,70 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
     }
     __builtin_amdgcn_sched_barrier(0);
   };
-  auto issue_tile = [&](auto stage, int k0, bool with_b) {
+  constexpr std::integral_constant<int, 0> c0{};
+  constexpr std::integral_constant<int, 1> c1{};
+  constexpr std::integral_constant<int, 2> c2{};
+  constexpr std::integral_constant<int, 3> c3{};
+  constexpr std::integral_constant<int, 4> c4{};
+  constexpr std::integral_constant<int, 5> c5{};
+  constexpr std::integral_constant<int, 6> c6{};
+  constexpr std::integral_constant<int, 7> c7{};
+  constexpr std::integral_constant<int, 8> c8{};
+  constexpr std::integral_constant<int, 9> c9{};
+  constexpr std::integral_constant<int, 10> c10{};
+  constexpr std::integral_constant<int, 11> c11{};
+  // prologue: A pairs (0,1) and (2,3), B tiles 0..2, row blocks 0,1 of the A pair (4,5)
 #pragma unroll
-    for (int q = 0; q < 4; ++q) issue_a(stage, k0, q);
-    if (with_b) {
+  for (int q = 0; q < 4; ++q) {
+    issue_a(c0, kclamp(0), q);
+    issue_a(c1, kclamp(1), q);
+  }
 #pragma unroll
-      for (int q = 0; q < 4; ++q) issue_b(stage, k0, q);
-    }
-  };
-  issue_tile(st0, kclamp(0), true);
-  issue_tile(st1, kclamp(1), true);
-  issue_tile(st2, kclamp(2), true);
-  issue_tile(st3, kclamp(3), false);
-  __builtin_amdgcn_s_waitcnt(0x4f74);   // vmcnt(20): tile 0 has landed
+  for (int q = 0; q < 4; ++q) issue_b(c0, kclamp(0), q);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    issue_a(c2, kclamp(2), q);
+    issue_a(c3, kclamp(3), q);
+  }
+#pragma unroll
+  for (int q = 0; q < 4; ++q) issue_b(c1, kclamp(1), q);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) issue_b(c2, kclamp(2), q);
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    issue_a(c4, kclamp(4), q);
+    issue_a(c5, kclamp(5), q);
+  }
+  __builtin_amdgcn_s_waitcnt(0x4f74);   // vmcnt(20): the first 12 loads, tile 0, have landed
   __syncthreads();
-  load_frags(st0, 0, 0);
-  for (int kt = 0; kt < KT; kt += 4) {
-    step(st0, st1, st3, kt);
-    step(st1, st2, st0, kt + 1);
-    step(st2, st3, st1, kt + 2);
-    step(st3, st0, st2, kt + 3);
+  load_frags(c0, c0, 0, 0);
+  int kt = 0;
+  for (; kt + 12 <= KT; kt += 12) {
+    step(c0, kt);
+    step(c1, kt + 1);
+    step(c2, kt + 2);
+    step(c3, kt + 3);
+    step(c4, kt + 4);
+    step(c5, kt + 5);
+    step(c6, kt + 6);
+    step(c7, kt + 7);
+    step(c8, kt + 8);
+    step(c9, kt + 9);
+    step(c10, kt + 10);
+    step(c11, kt + 11);
+  }
+  // the remaining 0, 4 or 8 steps (the stage phase is 0 again after whole trips of 12)
+  if (kt < KT) {
+    step(c0, kt);
+    step(c1, kt + 1);
+    step(c2, kt + 2);
+    step(c3, kt + 3);
+    if (kt + 4 < KT) {
+      step(c4, kt + 4);
+      step(c5, kt + 5);
+      step(c6, kt + 6);
+      step(c7, kt + 7);
+    }
   }
   __builtin_amdgcn_s_waitcnt(0);   // the clamped trailing loads must land before the block ends
   __syncthreads();
