@@ -120,13 +120,16 @@ __global__ __launch_bounds__(SCHED_THREADS) void ffn_schedule_kernel(
   if (i == 0) ws[0] = make_int4(total, 0, 0, 0);
 }
 
-__device__ __forceinline__ uint32_t bf16_rne(float x) {
-  uint32_t u = __float_as_uint(x);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return u >> 16;
-}
+// a * sigmoid(a) with the hardware reciprocal (1 ulp): the result is rounded to bf16 anyway
+__device__ __forceinline__ float silu(float a) { return a * __builtin_amdgcn_rcpf(1.0f + __expf(-a)); }
 
-__device__ __forceinline__ float silu(float a) { return a / (1.0f + __expf(-a)); }
+// two floats -> two bf16 (round to nearest even) in one 32-bit word, first argument in the low half
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
 
 // MODE 0: gate_up (+SwiGLU, bf16 out); MODE 1: down (fp32 or bf16 out)
 template <int MODE, bool OUT_BF16>
@@ -269,7 +272,8 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
       for (int nj = 0; nj < 4; ++nj) {
         const bf16x8 b = __builtin_bit_cast(
             bf16x8, __builtin_shufflevector(bl[buf][nj], bh[buf][nj], 0, 1, 2, 3, 4, 5, 6, 7));
-        acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][mi], b, acc[mi][nj], 0, 0, 0);
+        // weights as the first operand: the product comes out transposed, see the epilogue
+        acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, af[buf][mi], acc[mi][nj], 0, 0, 0);
       }
   };
 
@@ -353,7 +357,10 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
   constexpr std::integral_constant<int, 9> c9{};
   constexpr std::integral_constant<int, 10> c10{};
   constexpr std::integral_constant<int, 11> c11{};
-  // prologue: A pairs (0,1) and (2,3), B tiles 0..2, row blocks 0,1 of the A pair (4,5)
+  // prologue: A pairs (0,1) and (2,3), B tiles 0..2, row blocks 0,1 of the A pair (4,5) -- 32
+  // loads.  Their order matters for the counted waits: tile 0 is the first 12 loads, and B
+  // tile 1 must have at least 16 loads behind it by the barrier of step 0 (it has 20 with the
+  // B loads of that step), as every later tile has in the steady state.
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     issue_a(c0, kclamp(0), q);
@@ -362,12 +369,12 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
 #pragma unroll
   for (int q = 0; q < 4; ++q) issue_b(c0, kclamp(0), q);
 #pragma unroll
+  for (int q = 0; q < 4; ++q) issue_b(c1, kclamp(1), q);
+#pragma unroll
   for (int q = 0; q < 4; ++q) {
     issue_a(c2, kclamp(2), q);
     issue_a(c3, kclamp(3), q);
   }
-#pragma unroll
-  for (int q = 0; q < 4; ++q) issue_b(c1, kclamp(1), q);
 #pragma unroll
   for (int q = 0; q < 4; ++q) issue_b(c2, kclamp(2), q);
 #pragma unroll
@@ -409,41 +416,54 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
   __builtin_amdgcn_s_waitcnt(0);   // the clamped trailing loads must land before the block ends
   __syncthreads();
 
-  // ---- epilogue: lane holds column l32 of each 32x32 tile, rows 8*(v/4) + 4*(lane/32) + v%4
-  const int rsub = (lane / 32) * 4;
-  if (MODE == 0) {
-    uint16_t* H = (uint16_t*)out;
+  // ---- epilogue.  The MFMAs computed (X W)^T per 32 x 32 block, so a lane holds ONE token row
+  // (mi*32 + l32 of the wave's 128) and, in accumulator registers 4c .. 4c+3, FOUR consecutive
+  // weight columns 8c + 4*(lane/32) .. +3 of block nj.  Stored straight from there a row's
+  // bytes would leave in 8- or 16-byte pieces from different instructions; partial-line writes
+  // are slow in the L2.  Instead each wave passes its outputs, 32 rows at a time, through a
+  // 16 KB LDS region of its own (the A stages are free now) and reads them back with the lanes
+  // laid along the rows, so that every store instruction writes whole 128-byte lines.
+  // No barrier: the region is private to the wave and the LDS executes one wave's
+  // instructions in order.
+  constexpr int COLS = MODE == 0 ? 64 : 128;                    // output columns of this wave
+  constexpr int ESZ = (MODE == 0 || OUT_BF16) ? 2 : 4;
+  constexpr int ROW_BYTES = COLS * ESZ;                         // 128, 256 or 512
+  constexpr int CH = ROW_BYTES / 16;                            // 16-byte chunks per row
+  constexpr int RPI = 64 / CH;                                  // rows per store instruction
+  constexpr int SWZ_DIV = ROW_BYTES >= 256 ? 1 : 256 / ROW_BYTES;
+  // chunk q of row r sits at slot q ^ swz(r): spreads a column of pieces over all banks
+  auto swz = [&](int r) { return (r / SWZ_DIV) & (CH - 1); };
+  char* ep = wave == 0 ? lds_a0 : wave == 1 ? lds_a1 : wave == 2 ? lds_a2 : lds_a3;
+  const int csub = (lane / 32) * 4;
+  const int col0 = MODE == 0 ? nt * 128 + wn * 64 : nt * 256 + wn * 128;
+  const int rd_row = lane / CH, rd_chunk = lane % CH;
+  char* out_wave = (char*)out + ((size_t)(row0 + wm * 128) * ldo + col0) * ESZ;
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
+  for (int mi = 0; mi < 4; ++mi) {
+    char* wr = ep + l32 * ROW_BYTES;
+    const int sw = swz(l32);
 #pragma unroll
-      for (int nj = 0; nj < 2; ++nj) {
-        const int col = nt * 128 + wn * 64 + nj * 32 + l32;
+    for (int nj = 0; nj < (MODE == 0 ? 2 : 4); ++nj)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int r = wm * 128 + mi * 32 + 8 * (v / 4) + rsub + (v % 4);
-          if (r < rows) {
-            const float h = silu(acc[mi][nj][v]) * acc[mi][nj + 2][v];
-            H[(size_t)(row0 + r) * ldo + col] = (uint16_t)bf16_rne(h);
-          }
-        }
+      for (int c = 0; c < 4; ++c) {
+        const int boff = (nj * 32 + 8 * c + csub) * ESZ;        // byte offset of the piece in its row
+        char* dst = wr + ((((boff >> 4) ^ sw)) << 4) + (boff & 15);
+        float v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          v[i] = MODE == 0 ? silu(acc[mi][nj][4 * c + i]) * acc[mi][nj + 2][4 * c + i] : acc[mi][nj][4 * c + i];
+        if (ESZ == 2)
+          *(uint2*)dst = make_uint2(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]));
+        else
+          *(float4*)dst = make_float4(v[0], v[1], v[2], v[3]);
       }
-  } else {
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-      for (int nj = 0; nj < 4; ++nj) {
-        const int col = nt * 256 + wn * 128 + nj * 32 + l32;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int r = wm * 128 + mi * 32 + 8 * (v / 4) + rsub + (v % 4);
-          if (r < rows) {
-            if (OUT_BF16)
-              ((uint16_t*)out)[(size_t)(row0 + r) * ldo + col] = (uint16_t)bf16_rne(acc[mi][nj][v]);
-            else
-              ((float*)out)[(size_t)(row0 + r) * ldo + col] = acc[mi][nj][v];
-          }
-        }
-      }
+    for (int j = 0; j < 32 / RPI; ++j) {
+      const int r = j * RPI + rd_row;                            // row inside this pass
+      const uint4 v = *(const uint4*)(ep + r * ROW_BYTES + ((rd_chunk ^ swz(r)) << 4));
+      if (wm * 128 + mi * 32 + r < rows)
+        *(uint4*)(out_wave + (size_t)(mi * 32 + r) * ldo * ESZ + rd_chunk * 16) = v;
+    }
   }
 }
 

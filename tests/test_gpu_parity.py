@@ -165,6 +165,44 @@ def test_grouped_ffn_parity(sizes, d, f, yp_dtype):
     assert (H[R:].float() == 512.0).all() and (Yp[R:].float() == 512.0).all()
 
 
+@pytest.mark.parametrize("d,f,sizes", [(256, 128, [260, 3, 514, 0, 257]), (1024, 512, [260, 3, 514, 0, 257]),
+                                       (4096, 1536, [516] * 16), (3072, 2048, [516] * 16)])
+def test_grouped_ffn_short_tail_tiles_repeatable(d, f, sizes):
+    # Row tiles holding only a few rows make every A load hit the same cache lines, which shifts the
+    # timing of the load pipeline against the counted waits, most visibly when many blocks keep
+    # the memory system busy (the two large cases).  The k extents cover 0, 4 and 8 left-over
+    # steps after whole trips of the stage ring.  Every launch must give the same bytes, and the
+    # rows of the short tiles must match the oracle.
+    say(f"ffn short tail tiles d={d} f={f} sizes={sizes}")
+    G = len(sizes)
+    offsets = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    R = int(offsets[-1])
+    Xp = torch.randn((R, d), generator=torch.Generator().manual_seed(21)).to(torch.bfloat16)
+    W = make_weights(G, d, f, 23)
+    Wd = [tuple(m.to(DEV) for m in w) for w in W]
+    cols = [[w[i] for w in Wd] for i in range(3)]
+    Xd, od = Xp.to(DEV), torch.from_numpy(offsets).to(DEV)
+    H0 = Y0 = None
+    for it in range(20):
+        H = torch.zeros((R, f), dtype=torch.bfloat16, device=DEV)
+        Yp = torch.zeros((R, d), device=DEV)
+        fe.feplb_grouped_ffn(Xd, od, 0, G, d, f, *cols, H, Yp)
+        torch.cuda.synchronize()
+        if it == 0:
+            H0, Y0 = H, Yp
+        else:
+            assert torch.equal(H, H0) and torch.equal(Yp, Y0), f"launch {it} differs from launch 0"
+    # oracle on the rows of each group's last (short) tile only
+    tail = [np.arange(offsets[g] + max(sizes[g] - 1, 0) // 256 * 256, offsets[g + 1]) for g in range(G)]
+    rows = np.concatenate(tail)
+    off_t = np.concatenate([[0], np.cumsum([len(t) for t in tail])]).astype(np.int32)
+    H_o, Yp_o = orc.grouped_ffn(f64(Xp)[rows], off_t, [tuple(f64(m) for m in w) for w in W])
+    eh = bf16_rounding_excess(f64(H0)[rows], H_o)
+    ey = row_rel_err(f64(Y0)[rows], Yp_o)
+    say(f"  {len(rows)} tail rows: H rounding excess {eh:.3f} (<= 1)  Yp err {ey.max():.5f}")
+    assert eh <= 1.0 and ey.max() <= ROW_TOL
+
+
 def test_grouped_ffn_range_split_equals_one_call():
     # static range then dynamic range (two launches) gives the same bytes as one launch
     sizes = [200, 3, 0, 150, 90]
