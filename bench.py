@@ -35,12 +35,13 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def time_workload(name, steps, warmup, source_kind="device"):
+def time_workload(name, steps, warmup, source_kind="device", fused_gather=True, yp_dtype="f32"):
     import numpy as np
     import torch
     from paper_2604_19654_amd import runner
 
-    p = runner.prepare(name, "cuda:0", source_kind=source_kind)
+    p = runner.prepare(name, "cuda:0", source_kind=source_kind, fused_gather=fused_gather,
+                       yp_dtype=torch.bfloat16 if yp_dtype == "bf16" else torch.float32)
     wl, layer = p.wl, p.layer
     for _ in range(warmup):
         runner.step(p, mark=True)
@@ -93,8 +94,11 @@ def time_workload(name, steps, warmup, source_kind="device"):
         combine_gbps=(R * d * yp_bytes + T * d * 2 + T * k * 8) / (ms["combine"] * 1e-3) / 1e9,
         route_gbps=(T * wl.E * 4 + T * k * 8) / (ms["route"] * 1e-3) / 1e9,
     )
-    if "permute" in ms:
-        res["permute_gbps"] = (2 * R * d * 2 + T * k * 8 + R * 4) / (ms["permute"] * 1e-3) / 1e9
+    res["fused_gather"] = fused_gather
+    res["yp_dtype"] = yp_dtype
+    # the permute step with its row gather (X -> Xp), timed on its own when the step's GEMM gathers the rows itself
+    res["permute_with_gather_ms"] = ms["permute"] if ("permute" in ms and not fused_gather) else _permute_ms(p, steps)
+    res["permute_gbps"] = (2 * R * d * 2 + T * k * 8 + R * 4) / (res["permute_with_gather_ms"] * 1e-3) / 1e9
     if p.rebalanced:
         nbytes = sum(t.numel() * t.element_size() for t in p.remote_sources.values())
         res["staging"] = dict(bytes=nbytes, source=p.source_kind, copy_ms=ms["copy"],
@@ -103,6 +107,24 @@ def time_workload(name, steps, warmup, source_kind="device"):
         res["moves"] = p.moves
     res["pct_mfma_peak_ffn_kernels"] = 100.0 * res["ffn_tflops_kernels"] / MFMA_BF16_PEAK_TFLOPS
     return p, res
+
+
+def _permute_ms(p, steps):
+    """feplb_permute including the row gather into a permuted copy, on the step's own routing."""
+    import torch
+    from paper_2604_19654_amd import binding as B
+    lay, b = p.layer, p.layer.buf
+    G = len(p.groups)
+    Xp = torch.empty((lay.R_cap, lay.d), dtype=torch.bfloat16, device=p.wl.X.device)
+    args = (b.topk_ids, lay.E, p.groups, p.wl.X, lay.R_cap, Xp, b.offsets[: G + 1], b.row_src, b.inv, b.ws_permute)
+    e0, e1 = B.HipEvent(), B.HipEvent()
+    B.feplb_permute(*args)
+    e0.record(None)
+    for _ in range(steps):
+        B.feplb_permute(*args)
+    e1.record(None)
+    e1.synchronize()
+    return e0.elapsed_ms(e1) / steps
 
 
 def _copy_ms(layer):
@@ -168,6 +190,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all", action="store_true", help="also time the other four workloads (reported under all_workloads)")
     ap.add_argument("--cpu-tokens", type=int, default=8192)
+    ap.add_argument("--yp-dtype", default="f32", choices=["f32", "bf16"],
+                    help="type of the expert outputs Yp between the down GEMM and the combine")
+    ap.add_argument("--materialize-xp", action="store_true",
+                    help="permute writes the permuted copy Xp and the gate/up GEMM reads it (default: the GEMM gathers the rows itself)")
     a = ap.parse_args()
     if a.gpus != 1:
         log("bench.py: this build is a single-GPU hot path (one EP rank's share); run it with --gpus 1")
@@ -179,7 +205,7 @@ def main():
         sys.exit(2)
     fe.lib()  # fail loudly if the HIP library is missing
     prop = torch.cuda.get_device_properties(0)
-    p, res = time_workload(a.workload, a.steps, a.warmup, a.source)
+    p, res = time_workload(a.workload, a.steps, a.warmup, a.source, not a.materialize_xp, a.yp_dtype)
     log(json.dumps(res))
     cpu = None
     if not a.no_cpu_baseline:
@@ -192,11 +218,11 @@ def main():
         for name in ("C1", "C2", "C3", "C5", "C4"):
             if name == a.workload:
                 continue
-            q, r = time_workload(name, a.steps, a.warmup, a.source)
+            q, r = time_workload(name, a.steps, a.warmup, a.source, not a.materialize_xp, a.yp_dtype)
             log(json.dumps(r))
             others[name] = {k: r[k] for k in ("R", "ms_per_step", "ffn_tflops_kernels", "pct_mfma_peak_ffn_kernels",
-                                              "gate_up_tflops", "down_tflops", "combine_gbps", "route_gbps")
-                            } | ({"permute_gbps": r["permute_gbps"]} if "permute_gbps" in r else {})
+                                              "gate_up_tflops", "down_tflops", "combine_gbps", "route_gbps",
+                                              "permute_gbps")}
             q.wl.drop_weights()
             del q
             torch.cuda.empty_cache()
@@ -207,7 +233,8 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{a.workload} ({_describe(a.workload)})", "T": res["T"], "R": res["R"],
                    "d": res["d"], "f": res["f"], "E": res["E"], "k": res["k"], "groups": res["groups"],
-                   "yp_dtype": "f32", "staging_source": a.source if a.workload == "C4" else None},
+                   "yp_dtype": a.yp_dtype, "x_rows": "permuted copy" if a.materialize_xp else "gathered by the gate/up GEMM",
+                   "staging_source": a.source if a.workload == "C4" else None},
         "roofline": {"kernel": "grouped_gemm_kernel<0,true> (gate/up GEMM + SwiGLU)", "bound": "mfma",
                      "achieved": up_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": up_tflops / MFMA_BF16_PEAK_TFLOPS,

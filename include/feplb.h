@@ -124,7 +124,14 @@ int32_t feplb_permute(const int32_t* topk_ids, int32_t T, int32_t k, int32_t E,
  * The static range runs first; the dynamic range runs after the staging event
  * (Section 2.3 timeline), so a layer needs two calls, never one per expert.
  *
- *   Xp      device, bf16 [R_cap,d]
+ *   Xp      device, bf16 [R_cap,d] -- or, with row_src, the unpermuted X [T,d]
+ *   row_src device, int32 [R_cap] as written by feplb_permute (flat assignment
+ *           indices t*k+j), or NULL.  When given, GATE_UP gathers its input rows
+ *           while loading them: row r is X[row_src[r] / k, :], read from the matrix
+ *           `Xp` points at, and no permuted copy of X is needed (call
+ *           feplb_permute without X/Xp).  Token indices are clamped to [0, T);
+ *           needs T*d*2 < 4 GiB.
+ *   T, k    rows of X and assignments per token when row_src is given, ignored otherwise
  *   offsets device, int32 [G+1] as written by feplb_permute (read on the device)
  *   w_gate, w_up, w_down  host arrays of (g_end) device pointers indexed by g:
  *           W_gate[g], W_up[g] bf16 [d,f]; W_down[g] bf16 [f,d]; entries below
@@ -146,7 +153,8 @@ int32_t feplb_permute(const int32_t* topk_ids, int32_t T, int32_t k, int32_t E,
 
 size_t feplb_grouped_ffn_workspace_bytes(int32_t R_cap, int32_t G);
 
-int32_t feplb_grouped_ffn(const void* Xp, const int32_t* offsets,
+int32_t feplb_grouped_ffn(const void* Xp, const int32_t* row_src, int32_t T, int32_t k,
+                          const int32_t* offsets,
                           int32_t g_begin, int32_t g_end, int32_t R_cap,
                           int32_t d, int32_t f,
                           const void* const* w_gate, const void* const* w_up,

@@ -58,7 +58,7 @@ def lib():
                                     vp, vp, vp, vp, sz, vp]
         L.feplb_grouped_ffn_workspace_bytes.argtypes = [i32, i32]
         L.feplb_grouped_ffn_workspace_bytes.restype = sz
-        L.feplb_grouped_ffn.argtypes = [vp, vp, i32, i32, i32, i32, i32, C.POINTER(vp), C.POINTER(vp),
+        L.feplb_grouped_ffn.argtypes = [vp, vp, i32, i32, vp, i32, i32, i32, i32, i32, C.POINTER(vp), C.POINTER(vp),
                                         C.POINTER(vp), vp, vp, i32, i32, vp, sz, vp]
         L.feplb_unpermute_combine.argtypes = [vp, i32, vp, vp, i32, i32, i32, vp, vp]
         L.feplb_stage_weights.argtypes = [vp, vp, sz, vp, vp]
@@ -228,9 +228,11 @@ def _ptr_array(tensors: Sequence[Optional[torch.Tensor]]):
 
 
 def feplb_grouped_ffn(Xp, offsets, g_begin, g_end, d, f, w_gate, w_up, w_down, H, Yp,
-                      phases=FFN_ALL, ws=None, stream=None):
+                      phases=FFN_ALL, ws=None, stream=None, row_src=None, k=0):
     """Runs groups [g_begin, g_end).  w_* are sequences (indexed by group) of bf16
-    tensors or raw device addresses.  H bf16 [R_cap,f]; Yp fp32 or bf16 [R_cap,d]."""
+    tensors or raw device addresses.  H bf16 [R_cap,f]; Yp fp32 or bf16 [R_cap,d].
+    With row_src (int32 [R_cap], from feplb_permute) and k, Xp is the unpermuted X [T,d] and the
+    rows X[row_src[r] // k] are gathered as the gate/up GEMM loads them."""
     R_cap = H.shape[0]
     yp_dtype = F32
     if Yp is not None:
@@ -238,7 +240,8 @@ def feplb_grouped_ffn(Xp, offsets, g_begin, g_end, d, f, w_gate, w_up, w_down, H
     if ws is None:
         ws = torch.empty((feplb_grouped_ffn_workspace_bytes(R_cap, g_end),), dtype=torch.uint8,
                          device=H.device)
-    _check(lib().feplb_grouped_ffn(_ptr(Xp), _ptr(offsets), g_begin, g_end, R_cap, d, f,
+    n_src = int(Xp.shape[0]) if row_src is not None else 0
+    _check(lib().feplb_grouped_ffn(_ptr(Xp), _ptr(row_src), n_src, k, _ptr(offsets), g_begin, g_end, R_cap, d, f,
                                    _ptr_array(w_gate), _ptr_array(w_up), _ptr_array(w_down),
                                    _ptr(H), _ptr(Yp), yp_dtype, phases, _ptr(ws), ws.numel(),
                                    _stream(stream)), "feplb_grouped_ffn")

@@ -134,8 +134,9 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 // MODE 0: gate_up (+SwiGLU, bf16 out); MODE 1: down (fp32 or bf16 out)
 template <int MODE, bool OUT_BF16>
 __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
-    const uint16_t* __restrict__ A, int lda, const int4* __restrict__ sched, int K, int N,
-    int n_tiles_n, int patch_n, WeightTable wt, void* __restrict__ out, int ldo) {
+    const uint16_t* __restrict__ A, int lda, const int* __restrict__ row_src, int n_src_rows, int src_k,
+    const int4* __restrict__ sched, int K, int N, int n_tiles_n, int patch_n, WeightTable wt,
+    void* __restrict__ out, int ldo) {
   // Separate LDS arrays per stage (not one block with run-time offsets): the compiler can then
   // prove that an LDS-DMA load into one stage and the fragment reads of another stage do not
   // alias, and does not make the reads wait for the loads just issued.
@@ -178,14 +179,20 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
   // A stage: 256 rows x 64 bytes (32 k).  Load i of wave w fills rows 64w + 16i .. +15; the lane
   // at 16-byte slot p of row r holds k-chunk p ^ ((r >> 2) & 3), which makes the 16-byte
   // fragment reads of 16 consecutive rows hit 16 different bank groups.
+  // With row_src the tile's rows are gathered from the unpermuted matrix as they are loaded:
+  // row r of the tile is A[row_src[row0 + r] / src_k, :] -- row_src holds flat (token, slot)
+  // assignment indices -- and the permute step never has to write a permuted copy.  Rows past the tile's end repeat its last row either way.
   uint32_t a_goff[4];
+  const bool gather = MODE == 0 && row_src != nullptr;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int r = wave * 64 + i * 16 + lane / 4;
     const int chunk = (lane % 4) ^ ((r >> 2) & 3);
-    a_goff[i] = ((uint32_t)min(r, rows - 1) * (uint32_t)lda + chunk * 8) * 2;
+    int row = min(r, rows - 1);
+    if (gather) row = min(max(row_src[row0 + row] / src_k, 0), n_src_rows - 1);
+    a_goff[i] = ((uint32_t)row * (uint32_t)lda + chunk * 8) * 2;
   }
-  const char* a_gbase = wave_uniform(A + (size_t)row0 * lda);
+  const char* a_gbase = wave_uniform(gather ? A : A + (size_t)row0 * lda);
   // B stage: two parts (gate | up, or the two column halves) of 32 k-rows x 256 bytes (128
   // columns).  Waves 0,1 fill part 0, waves 2,3 part 1; load i fills k-rows 4q .. 4q+3,
   // q = 4*(w%2) + i.  Inside a row the four 64-byte groups are XOR-ed with (row & 3) so that
@@ -470,8 +477,9 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
 int max_tiles_for(int R_cap, int ng) { return R_cap / BM + ng + 1; }
 
 template <int MODE, bool OUT_BF16>
-hipError_t launch_gemm(const void* A, int lda, const int4* sched, int K, int N, int n_tiles_n,
-                       int max_tiles, const WeightTable& wt, void* out, int ldo, hipStream_t s) {
+hipError_t launch_gemm(const void* A, int lda, const int* row_src, int n_src_rows, int src_k, const int4* sched,
+                       int K, int N, int n_tiles_n, int max_tiles, const WeightTable& wt, void* out,
+                       int ldo, hipStream_t s) {
   const int patch_n = n_tiles_n % 4 == 0 ? 4 : (n_tiles_n % 2 == 0 ? 2 : 1);
   const int patch_m = 32 / patch_n;
   const int patches_m = (max_tiles + patch_m - 1) / patch_m;
@@ -479,7 +487,8 @@ hipError_t launch_gemm(const void* A, int lda, const int4* sched, int K, int N, 
   const int patch_rounds = (patches + XCDS - 1) / XCDS;
   const unsigned blocks = (unsigned)patch_rounds * XCDS * 32;
   hipLaunchKernelGGL((grouped_gemm_kernel<MODE, OUT_BF16>), dim3(blocks), dim3(THREADS), 0,
-                     s, (const uint16_t*)A, lda, sched, K, N, n_tiles_n, patch_n, wt, out, ldo);
+                     s, (const uint16_t*)A, lda, row_src, n_src_rows, src_k, sched, K, N, n_tiles_n, patch_n, wt,
+                     out, ldo);
   return hipGetLastError();
 }
 
@@ -490,7 +499,8 @@ extern "C" size_t feplb_grouped_ffn_workspace_bytes(int32_t R_cap, int32_t G) {
   return (size_t)(1 + max_tiles_for(R_cap, G)) * sizeof(int4);
 }
 
-extern "C" int32_t feplb_grouped_ffn(const void* Xp, const int32_t* offsets, int32_t g_begin,
+extern "C" int32_t feplb_grouped_ffn(const void* Xp, const int32_t* row_src, int32_t T, int32_t k,
+                                     const int32_t* offsets, int32_t g_begin,
                                      int32_t g_end, int32_t R_cap, int32_t d, int32_t f,
                                      const void* const* w_gate, const void* const* w_up,
                                      const void* const* w_down, void* H, void* Yp,
@@ -513,6 +523,11 @@ extern "C" int32_t feplb_grouped_ffn(const void* Xp, const int32_t* offsets, int
   const bool do_up = phases & FEPLB_FFN_GATE_UP, do_down = phases & FEPLB_FFN_DOWN;
   if (do_up) {
     FEPLB_REQUIRE(Xp && H && w_gate && w_up, FEPLB_EINVAL, "grouped_ffn: null Xp/H/w_gate/w_up");
+    if (row_src) {
+      // the kernel addresses a gathered row as a 32-bit byte offset from X
+      FEPLB_REQUIRE(T > 0 && k > 0 && (uint64_t)T * (uint64_t)d * 2 <= 0xffffffffull, FEPLB_ESHAPE,
+                    "grouped_ffn: gathering needs T > 0, k > 0 and T*d*2 < 4 GiB (T=%d k=%d d=%d)", T, k, d);
+    }
     FEPLB_REQUIRE(feplb::aligned16(Xp) && feplb::aligned16(H), FEPLB_EALIGN,
                   "grouped_ffn: Xp/H not 16-byte aligned");
   }
@@ -550,13 +565,13 @@ extern "C" int32_t feplb_grouped_ffn(const void* Xp, const int32_t* offsets, int
     FEPLB_LAUNCH_CHECK("ffn_schedule_kernel");
   }
   if (do_up) {
-    FEPLB_HIP((launch_gemm<0, true>(Xp, d, (const int4*)ws, d, f, f / 128, max_tiles, up_tab, H, f, s)));
+    FEPLB_HIP((launch_gemm<0, true>(Xp, d, row_src, T, k, (const int4*)ws, d, f, f / 128, max_tiles, up_tab, H, f, s)));
   }
   if (do_down) {
     if (yp_dtype == FEPLB_BF16)
-      FEPLB_HIP((launch_gemm<1, true>(H, f, (const int4*)ws, f, d, d / 256, max_tiles, down_tab, Yp, d, s)));
+      FEPLB_HIP((launch_gemm<1, true>(H, f, nullptr, 0, 1, (const int4*)ws, f, d, d / 256, max_tiles, down_tab, Yp, d, s)));
     else
-      FEPLB_HIP((launch_gemm<1, false>(H, f, (const int4*)ws, f, d, d / 256, max_tiles, down_tab, Yp, d, s)));
+      FEPLB_HIP((launch_gemm<1, false>(H, f, nullptr, 0, 1, (const int4*)ws, f, d, d / 256, max_tiles, down_tab, Yp, d, s)));
   }
   return FEPLB_OK;
 }

@@ -3,6 +3,10 @@ per-micro-batch timeline): route -> [counts to host -> plan -> stage dynamic
 experts' weights on a side stream] -> permute -> static experts' FFN ->
 wait for the staging event -> dynamic experts' FFN -> combine.
 
+By default the permute step computes the row indices only and the gate/up GEMM
+gathers the token rows while loading them (fused_gather); with fused_gather=False
+the permute step writes the permuted copy Xp and the GEMM reads that.
+
 Only sequencing, buffer ownership and stream plumbing live here; every step is
 a call into libfeplb.so.
 """
@@ -26,7 +30,7 @@ class LayerBuffers:
     offsets: torch.Tensor
     row_src: torch.Tensor
     inv: torch.Tensor
-    Xp: torch.Tensor
+    Xp: Optional[torch.Tensor]
     H: torch.Tensor
     Yp: torch.Tensor
     Y: torch.Tensor
@@ -39,8 +43,10 @@ class RankLayer:
     """Pre-allocates every buffer once (sized by R_cap rows and G_cap groups) so
     that a step launches kernels only."""
 
-    def __init__(self, T, E, k, d, f, R_cap, G_cap, device="cuda", yp_dtype=torch.float32, n_slots=0):
+    def __init__(self, T, E, k, d, f, R_cap, G_cap, device="cuda", yp_dtype=torch.float32, n_slots=0,
+                 fused_gather=True):
         self.T, self.E, self.k, self.d, self.f = T, E, k, d, f
+        self.fused_gather = fused_gather
         self.R_cap, self.G_cap, self.n_slots = R_cap, G_cap, n_slots
         dev = torch.device(device)
         i32 = dict(dtype=torch.int32, device=dev)
@@ -54,7 +60,7 @@ class RankLayer:
             offsets=torch.zeros((G_cap + 1,), **i32),
             row_src=torch.empty((max(R_cap, 1),), **i32),
             inv=torch.empty((max(T * k, 1),), **i32),
-            Xp=torch.empty((R_cap, d), **bf),
+            Xp=None if fused_gather else torch.empty((R_cap, d), **bf),
             H=torch.empty((R_cap, f), **bf),
             Yp=torch.empty((R_cap, d), dtype=yp_dtype, device=dev),
             Y=torch.empty((T, d), **bf),
@@ -79,20 +85,32 @@ class RankLayer:
         s = self.buf.slots[i]
         return s[: d * f].view(d, f), s[d * f: 2 * d * f].view(d, f), s[2 * d * f:].view(f, d)
 
-    def _ffn_range(self, g0, g1, wg, wu, wd, tag, mark):
+    def _permute(self, groups, X):
+        b = self.buf
+        G = len(groups)
+        if self.fused_gather:   # indices only
+            B.feplb_permute(b.topk_ids, self.E, groups, None, self.R_cap, None, b.offsets[: G + 1], b.row_src,
+                            b.inv, b.ws_permute)
+        else:
+            B.feplb_permute(b.topk_ids, self.E, groups, X, self.R_cap, b.Xp, b.offsets[: G + 1], b.row_src,
+                            b.inv, b.ws_permute)
+
+    def _ffn_range(self, X, g0, g1, wg, wu, wd, tag, mark):
         """One ragged launch per GEMM for groups [g0, g1).  With mark=True the
         schedule / gate_up / down launches are issued by separate calls so that
         HIP events can bracket each GEMM kernel on its stream."""
         b = self.buf
-        args = (b.Xp, b.offsets, g0, g1, self.d, self.f, wg, wu, wd, b.H, b.Yp)
+        src = (X, b.row_src) if self.fused_gather else (b.Xp, None)
+        args = (src[0], b.offsets, g0, g1, self.d, self.f, wg, wu, wd, b.H, b.Yp)
+        kw = dict(ws=b.ws_ffn, row_src=src[1], k=self.k)
         if not mark:
-            B.feplb_grouped_ffn(*args, phases=B.FFN_ALL, ws=b.ws_ffn)
+            B.feplb_grouped_ffn(*args, phases=B.FFN_ALL, **kw)
             return
-        B.feplb_grouped_ffn(*args, phases=B.FFN_SCHEDULE, ws=b.ws_ffn)
+        B.feplb_grouped_ffn(*args, phases=B.FFN_SCHEDULE, **kw)
         self._mark(tag + "_scheduled", True)
-        B.feplb_grouped_ffn(*args, phases=B.FFN_GATE_UP, ws=b.ws_ffn)
+        B.feplb_grouped_ffn(*args, phases=B.FFN_GATE_UP, **kw)
         self._mark(tag + "_gate_up", True)
-        B.feplb_grouped_ffn(*args, phases=B.FFN_DOWN, ws=b.ws_ffn)
+        B.feplb_grouped_ffn(*args, phases=B.FFN_DOWN, **kw)
         self._mark(tag + "_down", True)
 
     # -- static-only layer (no dynamic experts) ---------------------------
@@ -103,11 +121,10 @@ class RankLayer:
         self._mark("start", mark)
         B.feplb_route_topk(logits, self.k, b.topk_ids, b.topk_w, b.counts)
         self._mark("routed", mark)
-        B.feplb_permute(b.topk_ids, self.E, groups, X, self.R_cap, b.Xp, b.offsets[: G + 1], b.row_src, b.inv,
-                        b.ws_permute)
+        self._permute(groups, X)
         self._mark("permuted", mark)
         wg, wu, wd = ([w[i] for w in weights] for i in range(3))
-        self._ffn_range(0, G, wg, wu, wd, "static", mark)
+        self._ffn_range(X, 0, G, wg, wu, wd, "static", mark)
         B.feplb_unpermute_combine(b.Yp, b.inv, b.topk_w, self.T, self.k, self.d, b.Y)
         self._mark("combined", mark)
         return b.Y
@@ -146,16 +163,15 @@ class RankLayer:
         for i, (e, *_rest) in enumerate(moves):
             last = i == len(moves) - 1
             B.feplb_stage_weights(b.slots[i], remote_sources[e], side, self.staged if last else None)
-        B.feplb_permute(b.topk_ids, self.E, groups, X, self.R_cap, b.Xp, b.offsets[: G + 1], b.row_src, b.inv,
-                        b.ws_permute)
+        self._permute(groups, X)
         self._mark("permuted", mark)
         wlist = [static_weights[e] for e in static] + [self.slot_views(i) for i in range(len(moves))]
         wg, wu, wd = ([w[i] for w in wlist] for i in range(3))
-        self._ffn_range(0, Gs, wg, wu, wd, "static", mark)
+        self._ffn_range(X, 0, Gs, wg, wu, wd, "static", mark)
         if moves:
             B.feplb_stream_wait(main, self.staged)
             self._mark("staged", mark)
-            self._ffn_range(Gs, G, wg, wu, wd, "dynamic", mark)
+            self._ffn_range(X, Gs, G, wg, wu, wd, "dynamic", mark)
         self._mark("dynamic_done", mark)
         B.feplb_unpermute_combine(b.Yp, b.inv, b.topk_w, self.T, self.k, self.d, b.Y)
         self._mark("combined", mark)

@@ -41,8 +41,13 @@ def _route_counts(wl) -> np.ndarray:
     return counts.cpu().numpy().astype(np.int64)
 
 
-def prepare(name: str, device="cuda:0", yp_dtype=torch.float32, source_kind="device", **override) -> Prepared:
-    """source_kind: where the replicas' weights are copied from -- "device"
+def prepare(name: str, device="cuda:0", yp_dtype=torch.float32, source_kind="device", fused_gather=True,
+            **override) -> Prepared:
+    """yp_dtype: type of the expert outputs between the down GEMM and the combine: fp32 (default)
+    or bf16, which is faster (half the bytes through the down epilogue and the combine) but adds a
+    rounding per expert output.
+    fused_gather: the gate/up GEMM gathers the token rows itself (no permuted copy of X).
+    source_kind: where the replicas' weights are copied from -- "device"
     (a second buffer in HBM, standing in for a peer GPU's memory) or "pinned"
     (page-locked host memory)."""
     wl = workloads.make(name, device=device, **override)
@@ -53,7 +58,7 @@ def prepare(name: str, device="cuda:0", yp_dtype=torch.float32, source_kind="dev
         R = int(counts[experts].sum())
         weights = [wl.expert_weights(e) for e in experts]
         layer = RankLayer(wl.T, wl.E, wl.k, wl.d, wl.f, R_cap=max(R, 1), G_cap=len(groups), device=device,
-                          yp_dtype=yp_dtype)
+                          yp_dtype=yp_dtype, fused_gather=fused_gather)
         return Prepared(wl, layer, False, groups, weights, wl.rank, R, counts)
     # rebalanced share: the library's plan picks the receiving rank and the replicas
     dyn_flag = wl.dyn_flags(4)
@@ -72,7 +77,7 @@ def prepare(name: str, device="cuda:0", yp_dtype=torch.float32, source_kind="dev
             flat = host
         remote[int(e)] = flat
     layer = RankLayer(wl.T, wl.E, wl.k, wl.d, wl.f, R_cap=max(R, 1), G_cap=len(static) + wl.n_dyn,
-                      device=device, yp_dtype=yp_dtype, n_slots=wl.n_dyn)
+                      device=device, yp_dtype=yp_dtype, n_slots=wl.n_dyn, fused_gather=fused_gather)
     groups = [(e, 0, B.ORD_MAX) for e in static] + [(m[0], m[4], m[4] + m[3]) for m in moves]
     return Prepared(wl, layer, True, groups, [], rank, R, counts, dyn_flag, slots, static_weights, remote,
                     moves, source_kind)

@@ -203,6 +203,30 @@ def test_grouped_ffn_short_tail_tiles_repeatable(d, f, sizes):
     assert eh <= 1.0 and ey.max() <= ROW_TOL
 
 
+def test_grouped_ffn_gathering_rows_equals_reading_the_permuted_copy():
+    # row_src given: row r of the input is X[row_src[r] // k]; the bytes must equal a run on the
+    # materialised copy (the same MFMAs on the same operands)
+    T, k, d, f = 700, 4, 512, 256
+    sizes = [300, 0, 513, 5, 257]
+    G = len(sizes)
+    offsets = torch.tensor(np.concatenate([[0], np.cumsum(sizes)]), dtype=torch.int32, device=DEV)
+    R = int(sum(sizes))
+    g = torch.Generator().manual_seed(31)
+    X = torch.randn((T, d), generator=g).to(torch.bfloat16).to(DEV)
+    flat = torch.randint(0, T * k, (R,), generator=g, dtype=torch.int32).to(DEV)   # (token, slot) indices
+    Xp = X[(flat // k).long()].contiguous()
+    W = [tuple(m.to(DEV) for m in w) for w in make_weights(G, d, f, 33)]
+    cols = [[w[i] for w in W] for i in range(3)]
+    H1 = torch.zeros((R, f), dtype=torch.bfloat16, device=DEV); Y1 = torch.zeros((R, d), device=DEV)
+    H2 = torch.zeros_like(H1); Y2 = torch.zeros_like(Y1)
+    fe.feplb_grouped_ffn(Xp, offsets, 0, G, d, f, *cols, H1, Y1)
+    fe.feplb_grouped_ffn(X, offsets, 0, G, d, f, *cols, H2, Y2, row_src=flat, k=k)
+    torch.cuda.synchronize()
+    assert torch.equal(H1, H2) and torch.equal(Y1, Y2)
+    with pytest.raises(fe.FeplbError, match="gathering"):
+        fe.feplb_grouped_ffn(X, offsets, 0, G, d, f, *cols, H2, Y2, row_src=flat, k=0)
+
+
 def test_grouped_ffn_range_split_equals_one_call():
     # static range then dynamic range (two launches) gives the same bytes as one launch
     sizes = [200, 3, 0, 150, 90]
@@ -273,7 +297,8 @@ def oracle_layer(p, Y):
     assert np.array_equal(b.inv.cpu().numpy()[: wl.T * wl.k], inv), "inv"
     assert np.array_equal(b.row_src.cpu().numpy()[:R], row_src), "row_src"
     X64 = f64(wl.X)
-    assert torch.equal(b.Xp.cpu()[:R], wl.X.cpu()[torch.from_numpy(row_src.astype(np.int64) // wl.k)]), "Xp"
+    if b.Xp is not None:   # only written when the GEMM does not gather the rows itself
+        assert torch.equal(b.Xp.cpu()[:R], wl.X.cpu()[torch.from_numpy(row_src.astype(np.int64) // wl.k)]), "Xp"
     W = [tuple(f64(m) for m in wl.expert_weights(g[0])) for g in groups]
     H_o, Yp_o = orc.grouped_ffn(orc.gather_rows(X64, row_src, wl.k), offsets, W)
     want = orc.combine(Yp_o, inv, w, wl.T, wl.k)
@@ -283,7 +308,10 @@ def oracle_layer(p, Y):
     glob = np.abs(f64(Y) - want).max() / np.sqrt((want ** 2).mean())
     say(f"  {wl.name}: R={R} groups={np.diff(offsets).tolist()} H excess {eh:.3f} Yp {ey:.4f} "
         f"Y per-row {e.max():.4f} (bound {ROW_TOL}); max-abs/global-RMS {glob:.4f}")
-    assert eh <= 1.0 and ey <= ROW_TOL and e.max() <= ROW_TOL
+    # bf16 expert outputs (an option, not the default) add one rounding per combined term: the
+    # stated bound is kept for Yp itself, the combined rows get 1.5x of it
+    y_tol = ROW_TOL if b.Yp.dtype == torch.float32 else 1.5 * ROW_TOL
+    assert eh <= 1.0 and ey <= ROW_TOL and e.max() <= y_tol
     # tokens with no local slot are exactly +0
     none = np.nonzero((inv.reshape(wl.T, wl.k) < 0).all(axis=1))[0]
     assert np.all(Y.cpu().view(torch.int16).numpy()[none] == 0)
@@ -298,19 +326,21 @@ REDUCED = {
 }
 
 
+@pytest.mark.parametrize("fused_gather,yp_dtype", [(True, torch.bfloat16), (False, torch.bfloat16),
+                                                   (True, torch.float32), (False, torch.float32)])
 @pytest.mark.parametrize("name", list(REDUCED))
-def test_layer_parity_reduced(name):
-    say(f"layer {name} reduced {REDUCED[name]}")
-    p = runner.prepare(name, DEV, **REDUCED[name])
+def test_layer_parity_reduced(name, fused_gather, yp_dtype):
+    say(f"layer {name} reduced {REDUCED[name]} fused_gather={fused_gather} yp={yp_dtype}")
+    p = runner.prepare(name, DEV, fused_gather=fused_gather, yp_dtype=yp_dtype, **REDUCED[name])
     Y = runner.step(p)
     torch.cuda.synchronize()
     oracle_layer(p, Y)
 
 
-@pytest.mark.parametrize("source_kind", ["device", "pinned"])
-def test_rebalanced_layer_parity_reduced(source_kind):
-    say(f"layer C4 reduced, replicas staged from {source_kind} memory")
-    p = runner.prepare("C4", DEV, T=8 * 512, d=512, f=256, source_kind=source_kind)
+@pytest.mark.parametrize("source_kind,fused_gather", [("device", True), ("pinned", True), ("device", False)])
+def test_rebalanced_layer_parity_reduced(source_kind, fused_gather):
+    say(f"layer C4 reduced, replicas staged from {source_kind} memory, fused_gather={fused_gather}")
+    p = runner.prepare("C4", DEV, T=8 * 512, d=512, f=256, source_kind=source_kind, fused_gather=fused_gather)
     Y = runner.step(p)
     torch.cuda.synchronize()
     assert len(p.moves) == 4 and sum(m[3] for m in p.moves) > 0
@@ -380,7 +410,8 @@ def sampled_check(p, Y, stride):
     # Xp rows are byte copies: check a strided sample of rows against X
     rows = np.unique(np.concatenate([np.arange(0, R, 97), offsets[:-1][np.diff(offsets) > 0], offsets[1:][np.diff(offsets) > 0] - 1]))
     src_tok = torch.from_numpy(row_src[rows].astype(np.int64) // wl.k).to(DEV)
-    assert torch.equal(b.Xp[torch.from_numpy(rows).to(DEV)], wl.X[src_tok]), "Xp"
+    if b.Xp is not None:
+        assert torch.equal(b.Xp[torch.from_numpy(rows).to(DEV)], wl.X[src_tok]), "Xp"
     edge_rows = np.concatenate([offsets[:-1][np.diff(offsets) > 0], offsets[1:][np.diff(offsets) > 0] - 1])
     toks = np.unique(np.concatenate([np.arange(0, wl.T, stride), row_src[edge_rows] // wl.k, [wl.T - 1]]))
     keep = inv.reshape(wl.T, wl.k)[toks] >= 0
@@ -390,14 +421,18 @@ def sampled_check(p, Y, stride):
     e = row_rel_err(got, want)
     say(f"  {wl.name} full size: T={wl.T} R={R} groups={np.diff(offsets).tolist()} sampled tokens={len(toks)} "
         f"per-row err max {e.max():.4f} (bound {ROW_TOL})")
-    assert e.max() <= ROW_TOL
+    assert e.max() <= (ROW_TOL if b.Yp.dtype == torch.float32 else 1.5 * ROW_TOL)
     return e.max()
 
 
-@pytest.mark.parametrize("name,stride", [("C2", 16), ("C3", 16), ("C4", 256), ("C5", 64)])
-def test_layer_parity_full_size_sampled(name, stride):
-    say(f"layer {name} at full size")
-    p = runner.prepare(name, DEV)
+@pytest.mark.parametrize("name,stride,fused_gather,yp_dtype",
+                         [("C2", 16, True, torch.float32), ("C2", 16, False, torch.bfloat16),
+                          ("C3", 16, True, torch.float32), ("C4", 256, True, torch.float32),
+                          ("C4", 256, True, torch.bfloat16), ("C5", 64, True, torch.float32),
+                          ("C5", 64, False, torch.float32)])
+def test_layer_parity_full_size_sampled(name, stride, fused_gather, yp_dtype):
+    say(f"layer {name} at full size, fused_gather={fused_gather} yp={yp_dtype}")
+    p = runner.prepare(name, DEV, fused_gather=fused_gather, yp_dtype=yp_dtype)
     Y = runner.step(p)
     torch.cuda.synchronize()
     sampled_check(p, Y, stride)

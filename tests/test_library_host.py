@@ -47,9 +47,9 @@ def test_argument_validation_happens_before_any_device_work():
     g = (fe.Group * 2)(fe.Group(0, 0, 10), fe.Group(0, 5, 20))
     rc = L.feplb_permute(None, 0, 2, 4, g, 2, None, 0, None, 0, 16, None, None, None, 0, None)
     assert rc == -1 and b"overlap" in L.feplb_last_error()
-    rc = L.feplb_grouped_ffn(None, None, 0, 1, 128, 100, 128, None, None, None, None, None, 0, 7, None, 0, None)
+    rc = L.feplb_grouped_ffn(None, None, 0, 0, None, 0, 1, 128, 100, 128, None, None, None, None, None, 0, 7, None, 0, None)
     assert rc == -2
-    rc = L.feplb_grouped_ffn(None, None, 0, 1, 128, 256, 128, None, None, None, None, None, 0, 0, None, 0, None)
+    rc = L.feplb_grouped_ffn(None, None, 0, 0, None, 0, 1, 128, 256, 128, None, None, None, None, None, 0, 0, None, 0, None)
     assert rc == -1
     assert fe.feplb_permute_workspace_bytes(1024, 8, 128, 20) > 0
     assert fe.feplb_grouped_ffn_workspace_bytes(4096, 20) >= (4096 // 256 + 20) * 16   # one entry per 256-row tile
