@@ -27,7 +27,7 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch of the gate/up GEMM (read + written), measured with rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE and calibrated against the row-copy kernel of the same run; see
 # profiles/hbm_traffic_C4_pmc.md.  Only for the workload it was measured on.
-MEASURED_TRAFFIC_BYTES = {"C4": 5.317e9 + 0.270e9}
+MEASURED_TRAFFIC_BYTES = {"C4": 5.103e9 + 0.268e9}
 METRIC = "grouped-FFN TFLOP/s & % bf16 MFMA peak per rank share; permute/combine GB/s"
 
 
@@ -255,7 +255,7 @@ def main():
 
 def _gate_up_min_bytes(res):
     """Unique operand bytes of the gate/up GEMM per launch: both weight matrices of every
-    non-empty group once, Xp once, H written once (averaged over the launches of a step)."""
+    non-empty group once, every token row of the launch once, H written once (averaged over the launches of a step)."""
     groups = res.get("nonempty_groups", res["groups"])
     total = groups * 2 * res["d"] * res["f"] * 2 + res["R"] * res["d"] * 2 + res["R"] * res["f"] * 2
     return total / res["gate_up_launches_per_step"]
