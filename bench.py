@@ -65,7 +65,6 @@ def time_workload(name, steps, warmup, source_kind="device", fused_gather=True, 
             span("static_gate_up", "static_down", "down")
             span("dynamic_scheduled", "dynamic_gate_up", "gate_up")
             span("dynamic_gate_up", "dynamic_down", "down")
-            span("copy_start", "permuted", "_ignore")
             acc["copy"] = acc.get("copy", 0.0) + _copy_ms(layer)
             span("static_down", "staged", "wait_for_copy")
             span("dynamic_done", "combined", "combine")

@@ -469,7 +469,12 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
       const int r = j * RPI + rd_row;                            // row inside this pass
       const uint4 v = *(const uint4*)(ep + r * ROW_BYTES + ((rd_chunk ^ swz(r)) << 4));
       if (wm * 128 + mi * 32 + r < rows)
-        *(uint4*)(out_wave + (size_t)(mi * 32 + r) * ldo * ESZ + rd_chunk * 16) = v;
+        {
+          typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+          u32x4* dst = (u32x4*)(out_wave + (size_t)(mi * 32 + r) * ldo * ESZ + rd_chunk * 16);
+          const u32x4 vv = {v.x, v.y, v.z, v.w};
+          if (MODE == 1 && !OUT_BF16) __builtin_nontemporal_store(vv, dst); else *dst = vv;
+        }
     }
   }
 }

@@ -154,7 +154,12 @@ class RankLayer:
         Gs, G = len(static), len(static) + len(moves)
         if len(moves) > self.n_slots:
             raise B.FeplbError("more replicas than staging slots")
-        # weights of the replicas: copy engine, side stream, off the compute units
+        # the permute kernels go first: the GPU has been idle since the router finished
+        self._permute(groups, X)
+        self._mark("permuted", mark)
+        # weights of the replicas: copy engine, side stream, off the compute units.  The side
+        # stream waits for what is queued on the main stream (the previous step's readers of the
+        # slots; the few permute kernels above ride along).
         side = self.side_stream if overlap else main
         if overlap:
             side.wait_stream(main)
@@ -163,8 +168,6 @@ class RankLayer:
         for i, (e, *_rest) in enumerate(moves):
             last = i == len(moves) - 1
             B.feplb_stage_weights(b.slots[i], remote_sources[e], side, self.staged if last else None)
-        self._permute(groups, X)
-        self._mark("permuted", mark)
         wlist = [static_weights[e] for e in static] + [self.slot_views(i) for i in range(len(moves))]
         wg, wu, wd = ([w[i] for w in wlist] for i in range(3))
         self._ffn_range(X, 0, Gs, wg, wu, wd, "static", mark)
