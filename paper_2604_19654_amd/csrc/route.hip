@@ -8,6 +8,14 @@
 // at once.  Selection runs k rounds of "sub-group maximum of a 64-bit key";
 // the key orders by logit descending, then expert id ascending, so ties need
 // no extra pass.  HBM-bound in principle (T*E*4 bytes in, T*k*8 out).
+//
+// With many tokens (enough to give every SIMD a wavefront of them) a second kernel
+// routes one token per LANE instead: the lane streams its token's logits with 16-byte
+// loads in ascending expert order and keeps the k best so far as a sorted list in
+// registers.  A logit enters the list only if it is strictly greater than an entry, so
+// among equal logits the lower expert id stays ahead: the same total order, on plain
+// float compares (-0.0 equals +0.0), with a third of the instructions per token and no
+// cross-lane traffic.
 #include "common.h"
 
 namespace {
@@ -98,6 +106,120 @@ __global__ __launch_bounds__(256) void route_topk_kernel(const float* __restrict
   }
 }
 
+// Sorted insertion without branches: x enters before the first entry it is strictly greater than,
+// the entries from there on move down one place, the last one drops out.  above[i] = (x > v[i]) is
+// monotone in i because the list is sorted descending.
+template <int K>
+__device__ __forceinline__ void insert_sorted(float (&v)[K], int (&id)[K], float x, int e) {
+  float nv[K];
+  int ni[K];
+#pragma unroll
+  for (int i = 0; i < K; ++i) {
+    const bool above = x > v[i];
+    const bool above_prev = i > 0 ? x > v[i > 0 ? i - 1 : 0] : false;
+    const float shifted_v = above_prev ? v[i > 0 ? i - 1 : 0] : x;
+    const int shifted_i = above_prev ? id[i > 0 ? i - 1 : 0] : e;
+    nv[i] = above ? shifted_v : v[i];
+    ni[i] = above ? shifted_i : id[i];
+  }
+#pragma unroll
+  for (int i = 0; i < K; ++i) {
+    v[i] = nv[i];
+    id[i] = ni[i];
+  }
+}
+
+// One token per lane.  K = k exactly; E a multiple of 32; logits 16-byte aligned.
+// A wavefront owns 64 consecutive tokens.  Reading a token's row straight into its lane would
+// touch 64 different memory lines per load instruction; instead the wavefront loads 32 logits of
+// all its tokens at a time as whole lines (8 lanes per 128-byte line), parks them in 8 KB of LDS
+// of its own and each lane reads its token's 32 values back.  16-byte slot p of token tk sits at
+// slot p ^ (tk & 7), which spreads the 16-byte reads of 16 consecutive tokens over the banks.
+constexpr int LANE_WAVES = 2;   // wavefronts per block
+template <int K>
+__global__ __launch_bounds__(LANE_WAVES * 64) void route_topk_lane_kernel(
+    const float* __restrict__ logits, int T, int E, int* __restrict__ ids, float* __restrict__ w,
+    int* __restrict__ counts) {
+  extern __shared__ int hist[];
+  __shared__ __attribute__((aligned(16))) float stage[LANE_WAVES][64 * 32];
+  const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
+  if (counts) {
+    for (int e = tid; e < E; e += LANE_WAVES * 64) hist[e] = 0;
+    __syncthreads();
+  }
+  const long long t_wave = ((long long)blockIdx.x * LANE_WAVES + wave) * 64;
+  const long long t = t_wave + lane;
+  float v[K];
+  int id[K];
+#pragma unroll
+  for (int i = 0; i < K; ++i) {
+    v[i] = -INFINITY;   // below every finite logit; E >= K fills all entries
+    id[i] = 0;
+  }
+  auto insert = [&](float x, int e) { insert_sorted<K>(v, id, x, e); };
+  // load i of a chunk: token t_wave + 8*i + lane/8 (clamped to the last token), 16-byte piece lane%8
+  const int piece = lane % 8;
+  typedef float f32x4 __attribute__((ext_vector_type(4)));   // a plain vector type stays in registers
+  const f32x4* src[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    long long tk = t_wave + 8 * i + lane / 8;
+    if (tk > T - 1) tk = T - 1;
+    src[i] = (const f32x4*)(logits + tk * E) + piece;
+  }
+  f32x4* const st = (f32x4*)stage[wave];
+  f32x4 buf[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) buf[i] = src[i][0];
+  for (int c0 = 0; c0 < E; c0 += 32) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int tk = 8 * i + lane / 8;
+      st[tk * 8 + (piece ^ (tk & 7))] = buf[i];
+    }
+    // next chunk (the last trip re-reads its own: no branch)
+    const int next = min(c0 + 32, E - 32) / 4;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) buf[i] = src[i][next];
+    __builtin_amdgcn_wave_barrier();   // the LDS runs a wavefront's accesses in order; this keeps the compiler from reordering them
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+      const f32x4 x = st[lane * 8 + (p ^ (lane & 7))];
+      insert(x.x, c0 + 4 * p);
+      insert(x.y, c0 + 4 * p + 1);
+      insert(x.z, c0 + 4 * p + 2);
+      insert(x.w, c0 + 4 * p + 3);
+    }
+    __builtin_amdgcn_wave_barrier();
+  }
+  if (t < T) {
+    float p[K], sum = 0.f;
+#pragma unroll
+    for (int j = 0; j < K; ++j) {
+      p[j] = expf(v[j] - v[0]);
+      sum += p[j];
+    }
+#pragma unroll
+    for (int j = 0; j < K; ++j) {
+      ids[t * K + j] = id[j];
+      w[t * K + j] = p[j] / sum;
+      if (counts) atomicAdd(&hist[id[j]], 1);
+    }
+  }
+  if (counts) {
+    __syncthreads();
+    for (int e = tid; e < E; e += LANE_WAVES * 64)
+      if (hist[e]) atomicAdd(&counts[e], hist[e]);
+  }
+}
+
+template <int K>
+void launch_lane(const float* logits, int T, int E, int* ids, float* w, int* counts, hipStream_t s) {
+  const int per = LANE_WAVES * 64;
+  hipLaunchKernelGGL((route_topk_lane_kernel<K>), dim3((unsigned)((T + per - 1) / per)), dim3(per),
+                     counts ? (size_t)E * sizeof(int) : 0, s, logits, T, E, ids, w, counts);
+}
+
 __global__ void zero_i32_kernel(int* p, int n) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = 0;
@@ -147,6 +269,14 @@ extern "C" int32_t feplb_route_topk(const float* logits, int32_t T, int32_t E, i
   }
   if (T == 0) return FEPLB_OK;
   FEPLB_REQUIRE(logits && topk_ids && topk_w, FEPLB_EINVAL, "route_topk: null buffer");
+  // enough tokens to occupy a good part of the chip with one token per lane (a wavefront = 64 tokens)
+  if (T >= 16384 && E % 32 == 0 && ((uintptr_t)logits & 15) == 0 && (k == 2 || k == 4 || k == 8)) {
+    if (k == 2) launch_lane<2>(logits, T, E, topk_ids, topk_w, counts, s);
+    else if (k == 4) launch_lane<4>(logits, T, E, topk_ids, topk_w, counts, s);
+    else launch_lane<8>(logits, T, E, topk_ids, topk_w, counts, s);
+    FEPLB_LAUNCH_CHECK("route_topk_lane_kernel");
+    return FEPLB_OK;
+  }
   // sub-group width: at least k lanes (lane j keeps result j), and wide enough
   // that a lane holds at most 8 logits (16 for the largest E).
   int sg = next_pow2(k);

@@ -21,7 +21,11 @@ def say(*a):
 
 # ------------------------------------------------------------------ routing
 @pytest.mark.parametrize("T,E,k", [(512, 8, 2), (1000, 128, 8), (77, 5, 5), (300, 64, 1), (129, 200, 6),
-                                   (64, 1024, 32), (33, 16, 16), (1, 128, 8), (4099, 128, 8), (257, 3, 2)])
+                                   (64, 1024, 32), (33, 16, 16), (1, 128, 8), (4099, 128, 8), (257, 3, 2),
+                                   # from 16384 tokens on, a kernel with one token per lane takes over
+                                   # (E a multiple of 32, k in {2, 4, 8}; other shapes stay with the first)
+                                   (16384 + 37, 128, 8), (70001, 64, 2), (20000, 32, 4), (16384, 8, 8),
+                                   (16500, 130, 8), (16384, 128, 8)])
 def test_route_topk_parity(T, E, k):
     say(f"route T={T} E={E} k={k}")
     g = torch.Generator().manual_seed(T * 31 + E)
