@@ -5,7 +5,7 @@
 // The row order is fully determined (groups in table order, ascending flat
 // assignment inside a group), so no atomics may decide a row position.  It is a
 // stable counting sort over the flat assignments a = t*k + j, split in chunks
-// of CHUNK assignments, one wavefront per chunk:
+// of 256 or 1024 assignments (by batch size), one wavefront per chunk:
 //   1. chunk_hist : per-chunk, per-expert counts (LDS histogram per wave)
 //   2. chunk_scan : per expert, exclusive prefix over chunks -> the ordinal of
 //                   the first occurrence in each chunk, and the expert's total
@@ -21,7 +21,9 @@
 
 namespace {
 
-constexpr int CHUNK = 1024;          // assignments per wavefront
+// assignments per wavefront: small batches get shorter chunks, i.e. more wavefronts for the
+// serial walk of assign_rows (a multiple of 64 either way)
+int chunk_for(long long A) { return A <= (1ll << 18) ? 256 : 1024; }
 constexpr int WAVES = 4;             // wavefronts per block
 constexpr int BLOCK = WAVES * 64;
 
@@ -32,7 +34,7 @@ struct GroupTable {
 };
 
 __global__ __launch_bounds__(BLOCK) void chunk_hist_kernel(const int* __restrict__ ids,
-                                                           long long A, int E, int nchunks,
+                                                           long long A, int E, int nchunks, int chunk,
                                                            int* __restrict__ chunk_hist) {
   extern __shared__ int lds[];
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
@@ -41,8 +43,8 @@ __global__ __launch_bounds__(BLOCK) void chunk_hist_kernel(const int* __restrict
   for (int e = lane; e < E; e += 64) h[e] = 0;
   __builtin_amdgcn_wave_barrier();
   if (c < nchunks) {
-    const long long a0 = (long long)c * CHUNK;
-    for (int i = lane; i < CHUNK; i += 64) {
+    const long long a0 = (long long)c * chunk;
+    for (int i = lane; i < chunk; i += 64) {
       const long long a = a0 + i;
       if (a < A) {
         const int e = ids[a];
@@ -133,7 +135,7 @@ __global__ __launch_bounds__(FEPLB_MAX_GROUPS) void group_offsets_kernel(
 }
 
 __global__ __launch_bounds__(BLOCK) void assign_rows_kernel(
-    const int* __restrict__ ids, long long A, int E, int G, int nchunks,
+    const int* __restrict__ ids, long long A, int E, int G, int nchunks, int chunk,
     const int* __restrict__ chunk_base, const int* __restrict__ meta, int R_cap,
     int* __restrict__ row_src, int* __restrict__ inv) {
   extern __shared__ int lds[];
@@ -154,9 +156,9 @@ __global__ __launch_bounds__(BLOCK) void assign_rows_kernel(
   if (c >= nchunks) return;
   int nbits = 0;
   while ((1 << nbits) < E) ++nbits;
-  const long long a0 = (long long)c * CHUNK;
+  const long long a0 = (long long)c * chunk;
   const unsigned long long below = (1ull << lane) - 1ull;
-  for (int i = 0; i < CHUNK; i += 64) {
+  for (int i = 0; i < chunk; i += 64) {
     const long long a = a0 + i + lane;
     if (a0 + i >= A) break;  // uniform across the wave
     int e = -1;
@@ -223,13 +225,14 @@ __global__ __launch_bounds__(BLOCK) void gather_rows_kernel(const u32x4* __restr
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct Layout {
-  int nchunks;
+  int nchunks, chunk;
   size_t hist_off, total_off, meta_off, bytes;
 };
 
 Layout layout(long long A, int E, int G) {
   Layout L;
-  L.nchunks = (int)((A + CHUNK - 1) / CHUNK);
+  L.chunk = chunk_for(A);
+  L.nchunks = (int)((A + L.chunk - 1) / L.chunk);
   size_t off = 0;
   L.hist_off = off;
   off = align_up(off + (size_t)(L.nchunks > 0 ? L.nchunks : 1) * E * sizeof(int), 256);
@@ -295,7 +298,7 @@ extern "C" int32_t feplb_permute(const int32_t* topk_ids, int32_t T, int32_t k, 
   const int cblocks = (L.nchunks + WAVES - 1) / WAVES;
   if (L.nchunks > 0) {
     hipLaunchKernelGGL(chunk_hist_kernel, dim3(cblocks), dim3(BLOCK),
-                       (size_t)WAVES * E * sizeof(int), s, topk_ids, A, E, L.nchunks, hist);
+                       (size_t)WAVES * E * sizeof(int), s, topk_ids, A, E, L.nchunks, L.chunk, hist);
     FEPLB_LAUNCH_CHECK("chunk_hist_kernel");
   }
   hipLaunchKernelGGL(chunk_scan_kernel, dim3((E + WAVES - 1) / WAVES), dim3(BLOCK), 0, s, hist, E,
@@ -307,7 +310,7 @@ extern "C" int32_t feplb_permute(const int32_t* topk_ids, int32_t T, int32_t k, 
   if (L.nchunks > 0) {
     const size_t lds = ((size_t)WAVES * E + E + 4 * (size_t)G) * sizeof(int);
     hipLaunchKernelGGL(assign_rows_kernel, dim3(cblocks), dim3(BLOCK), lds, s, topk_ids, A, E, G,
-                       L.nchunks, hist, meta, R_cap, row_src, inv);
+                       L.nchunks, L.chunk, hist, meta, R_cap, row_src, inv);
     FEPLB_LAUNCH_CHECK("assign_rows_kernel");
   }
   if (X && Xp && R_cap > 0 && d > 0) {
