@@ -16,6 +16,7 @@ import torch
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ORD_MAX = 2**31 - 1
+MAX_GROUPS = 128   # FEPLB_MAX_GROUPS
 F32, BF16 = 0, 1
 FFN_GATE_UP, FFN_DOWN, FFN_SCHEDULE, FFN_ALL = 1, 2, 4, 7
 PLAN_WHOLE, PLAN_OVERFLOW = 0, 1
