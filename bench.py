@@ -35,7 +35,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def time_workload(name, steps, warmup, source_kind="device", fused_gather=True, yp_dtype="f32"):
+def time_workload(name, steps, warmup, source_kind="device", fused_gather=True, yp_dtype="f32", early_static=True):
     import numpy as np
     import torch
     from paper_2604_19654_amd import runner
@@ -44,13 +44,13 @@ def time_workload(name, steps, warmup, source_kind="device", fused_gather=True, 
                        yp_dtype=torch.bfloat16 if yp_dtype == "bf16" else torch.float32)
     wl, layer = p.wl, p.layer
     for _ in range(warmup):
-        runner.step(p, mark=True)
+        runner.step(p, mark=True, early_static=early_static)
     torch.cuda.synchronize()
     tl = layer.timeline
     acc = {}
     t0 = time.perf_counter()
     for _ in range(steps):
-        runner.step(p, mark=True)
+        runner.step(p, mark=True, early_static=early_static)
         # the step's events are complete once the stream drains; reading them costs one sync per
         # step, which a rebalanced step already pays for its counts read-back
         tl["combined"].synchronize()
@@ -68,7 +68,9 @@ def time_workload(name, steps, warmup, source_kind="device", fused_gather=True, 
             acc["copy"] = acc.get("copy", 0.0) + _copy_ms(layer)
             span("static_down", "staged", "wait_for_copy")
             span("dynamic_done", "combined", "combine")
-            span("routed", "permuted", "plan_stage_permute")
+            # plan first: counts read-back, host plan and the permute of all groups; early static
+            # launch: the permute of the static groups only (the rest happens behind the static FFN)
+            span("routed", "permuted", "permute_static" if early_static else "plan_stage_permute")
         else:
             span("routed", "permuted", "permute")
             span("static_scheduled", "static_gate_up", "gate_up")
@@ -191,6 +193,8 @@ def main():
     ap.add_argument("--cpu-tokens", type=int, default=8192)
     ap.add_argument("--yp-dtype", default="f32", choices=["f32", "bf16"],
                     help="type of the expert outputs Yp between the down GEMM and the combine")
+    ap.add_argument("--plan-first", action="store_true",
+                    help="rebalanced share: wait for the host plan before permuting anything (default: the static experts start before the plan is known)")
     ap.add_argument("--materialize-xp", action="store_true",
                     help="permute writes the permuted copy Xp and the gate/up GEMM reads it (default: the GEMM gathers the rows itself)")
     a = ap.parse_args()
@@ -204,7 +208,7 @@ def main():
         sys.exit(2)
     fe.lib()  # fail loudly if the HIP library is missing
     prop = torch.cuda.get_device_properties(0)
-    p, res = time_workload(a.workload, a.steps, a.warmup, a.source, not a.materialize_xp, a.yp_dtype)
+    p, res = time_workload(a.workload, a.steps, a.warmup, a.source, not a.materialize_xp, a.yp_dtype, not a.plan_first)
     log(json.dumps(res))
     cpu = None
     if not a.no_cpu_baseline:
@@ -217,7 +221,7 @@ def main():
         for name in ("C1", "C2", "C3", "C5", "C4"):
             if name == a.workload:
                 continue
-            q, r = time_workload(name, a.steps, a.warmup, a.source, not a.materialize_xp, a.yp_dtype)
+            q, r = time_workload(name, a.steps, a.warmup, a.source, not a.materialize_xp, a.yp_dtype, not a.plan_first)
             log(json.dumps(r))
             others[name] = {k: r[k] for k in ("R", "ms_per_step", "ffn_tflops_kernels", "pct_mfma_peak_ffn_kernels",
                                               "gate_up_tflops", "down_tflops", "combine_gbps", "route_gbps",
@@ -233,6 +237,7 @@ def main():
         "config": {"workload": f"{a.workload} ({_describe(a.workload)})", "T": res["T"], "R": res["R"],
                    "d": res["d"], "f": res["f"], "E": res["E"], "k": res["k"], "groups": res["groups"],
                    "yp_dtype": a.yp_dtype, "x_rows": "permuted copy" if a.materialize_xp else "gathered by the gate/up GEMM",
+                   "schedule": ("plan first" if a.plan_first else "static experts launched before the plan") if a.workload == "C4" else None,
                    "staging_source": a.source if a.workload == "C4" else None},
         "roofline": {"kernel": "grouped_gemm_kernel<0,true> (gate/up GEMM + SwiGLU)", "bound": "mfma",
                      "achieved": up_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",

@@ -113,6 +113,25 @@ int32_t feplb_permute(const int32_t* topk_ids, int32_t T, int32_t k, int32_t E,
                       int32_t* offsets, int32_t* row_src, int32_t* inv,
                       void* ws, size_t ws_bytes, void* stream);
 
+/* Section 2.3, per-micro-batch timeline: the static experts' computation does not depend
+ * on the rebalancing plan, so it can be permuted and started before the plan is known; the
+ * dynamic experts' groups are added once it is.  feplb_permute_append takes the same
+ * arguments as feplb_permute for those later groups and differs in three points:
+ *   - offsets[0] is an INPUT read on the device: the row at which these groups start (the
+ *     end of the earlier call, i.e. pass that call's `offsets + G_earlier`); offsets[1..G]
+ *     are written as before;
+ *   - inv entries of assignments that match none of THESE groups are left as they are, so the
+ *     earlier call's rows survive (no assignment may match groups of both calls);
+ *   - with X/Xp, only rows [offsets[0], offsets[G]) of Xp are written.
+ * R_cap still bounds the highest row written.  Uses the same workspace size; the two calls may
+ * share a workspace if they are ordered on the device.
+ */
+int32_t feplb_permute_append(const int32_t* topk_ids, int32_t T, int32_t k, int32_t E,
+                             const feplb_group* groups, int32_t G,
+                             const void* X, int32_t d, void* Xp, int32_t R_cap,
+                             int32_t* offsets, int32_t* row_src, int32_t* inv,
+                             void* ws, size_t ws_bytes, void* stream);
+
 /* ------------------------------------------------------------------ expert FFN
  * Section 3.1: expert compute is a Grouped GEMM; Section 2.3: its efficiency
  * depends on each expert's batch size and per-expert launches fragment it

@@ -57,6 +57,7 @@ def lib():
         L.feplb_permute_workspace_bytes.restype = sz
         L.feplb_permute.argtypes = [vp, i32, i32, i32, C.POINTER(Group), i32, vp, i32, vp, i32,
                                     vp, vp, vp, vp, sz, vp]
+        L.feplb_permute_append.argtypes = L.feplb_permute.argtypes
         L.feplb_grouped_ffn_workspace_bytes.argtypes = [i32, i32]
         L.feplb_grouped_ffn_workspace_bytes.restype = sz
         L.feplb_grouped_ffn.argtypes = [vp, vp, i32, i32, vp, i32, i32, i32, i32, i32, C.POINTER(vp), C.POINTER(vp),
@@ -68,7 +69,7 @@ def lib():
         L.feplb_expert_bytes.restype = sz
         L.feplb_plan.argtypes = [i32, i32, vp, vp, vp, vp, i64, i32, i32, C.POINTER(Move), i32,
                                  C.POINTER(i32), vp, vp, C.POINTER(i32)]
-        for name in ("feplb_route_topk", "feplb_permute", "feplb_grouped_ffn", "feplb_unpermute_combine",
+        for name in ("feplb_route_topk", "feplb_permute", "feplb_permute_append", "feplb_grouped_ffn", "feplb_unpermute_combine",
                      "feplb_stage_weights", "feplb_stream_wait", "feplb_plan"):
             getattr(L, name).restype = i32
         _LIB = L
@@ -190,8 +191,12 @@ def _group_array(groups: Sequence):
 
 
 def feplb_permute(topk_ids, E, groups, X, R_cap, Xp=None, offsets=None, row_src=None, inv=None,
-                  ws=None, stream=None):
-    """-> (Xp bf16 [R_cap,d], offsets int32 [G+1], row_src int32 [R_cap], inv int32 [T*k])."""
+                  ws=None, stream=None, append=False):
+    """-> (Xp bf16 [R_cap,d], offsets int32 [G+1], row_src int32 [R_cap], inv int32 [T*k]).
+    append=True calls feplb_permute_append: offsets[0] is then the (device-side) row these groups
+    start at, and offsets, row_src and inv must be the earlier call's buffers."""
+    if append and (offsets is None or row_src is None or inv is None):
+        raise FeplbError("feplb_permute(append=True) continues an earlier call: pass its offsets view, row_src and inv")
     _need(topk_ids, torch.int32, "topk_ids")
     T, k = topk_ids.shape
     G = len(groups)
@@ -211,9 +216,10 @@ def feplb_permute(topk_ids, E, groups, X, R_cap, Xp=None, offsets=None, row_src=
     need = feplb_permute_workspace_bytes(T, k, E, G)
     if ws is None:
         ws = torch.empty((need,), dtype=torch.uint8, device=dev)
-    _check(lib().feplb_permute(_ptr(topk_ids), T, k, E, _group_array(groups), G, _ptr(X), d, _ptr(Xp),
-                               R_cap, _ptr(offsets), _ptr(row_src), _ptr(inv), _ptr(ws), ws.numel(),
-                               _stream(stream)), "feplb_permute")
+    fn = lib().feplb_permute_append if append else lib().feplb_permute
+    _check(fn(_ptr(topk_ids), T, k, E, _group_array(groups), G, _ptr(X), d, _ptr(Xp),
+              R_cap, _ptr(offsets), _ptr(row_src), _ptr(inv), _ptr(ws), ws.numel(),
+              _stream(stream)), "feplb_permute_append" if append else "feplb_permute")
     return Xp, offsets, row_src, inv
 
 

@@ -85,10 +85,13 @@ __global__ __launch_bounds__(BLOCK) void chunk_scan_kernel(int* __restrict__ chu
 
 // meta layout (ints): head[E] | next[G] | lo[G] | hi[G] | start[G]
 __global__ __launch_bounds__(FEPLB_MAX_GROUPS) void group_offsets_kernel(
-    GroupTable tab, int G, int E, const int* __restrict__ total, int* __restrict__ offsets,
-    int* __restrict__ meta) {
+    GroupTable tab, int G, int E, const int* __restrict__ total, int* offsets,
+    int* __restrict__ meta, int append) {
   __shared__ int scan[FEPLB_MAX_GROUPS];
   const int g = threadIdx.x;
+  // appending: the rows of these groups follow those of an earlier call, whose end is offsets[0]
+  const int base = append ? offsets[0] : 0;
+  __syncthreads();   // every thread has read the base before offsets[0] is written again
   int size = 0, lo = 0, hi = 0, e = -1;
   if (g < G) {
     e = tab.g[g].expert;
@@ -111,14 +114,14 @@ __global__ __launch_bounds__(FEPLB_MAX_GROUPS) void group_offsets_kernel(
   int* ghi = glo + G;
   int* gstart = ghi + G;
   if (g < G) {
-    const int off = scan[g] - size;
+    const int off = base + scan[g] - size;
     offsets[g] = off;
     glo[g] = lo;
     ghi[g] = hi;
     gstart[g] = off - lo;  // row = start + ordinal
-    if (g == G - 1) offsets[G] = scan[g];
+    if (g == G - 1) offsets[G] = base + scan[g];
   }
-  if (G == 0 && g == 0) offsets[0] = 0;
+  if (G == 0 && g == 0) offsets[0] = base;
   for (int i = g; i < E; i += FEPLB_MAX_GROUPS) head[i] = -1;
   __syncthreads();
   if (g == 0) {
@@ -137,7 +140,7 @@ __global__ __launch_bounds__(FEPLB_MAX_GROUPS) void group_offsets_kernel(
 __global__ __launch_bounds__(BLOCK) void assign_rows_kernel(
     const int* __restrict__ ids, long long A, int E, int G, int nchunks, int chunk,
     const int* __restrict__ chunk_base, const int* __restrict__ meta, int R_cap,
-    int* __restrict__ row_src, int* __restrict__ inv) {
+    int* __restrict__ row_src, int* __restrict__ inv, int append) {
   extern __shared__ int lds[];
   // LDS: run[WAVES][E] | head[E] | next[G] lo[G] hi[G] start[G]
   volatile int* run_all = lds;
@@ -186,7 +189,7 @@ __global__ __launch_bounds__(BLOCK) void assign_rows_kernel(
     }
     __builtin_amdgcn_wave_barrier();
     if (a < A) {
-      inv[a] = row;
+      if (!append || row >= 0) inv[a] = row;   // appending leaves the other calls' entries alone
       if (row >= 0 && row < R_cap) row_src[row] = (int)a;
     }
   }
@@ -201,7 +204,7 @@ __global__ __launch_bounds__(BLOCK) void gather_rows_kernel(const u32x4* __restr
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
   const long long r = (long long)blockIdx.x * WAVES + wave;
   const int R = min(offsets[G], R_cap);
-  if (r >= R) return;
+  if (r < offsets[0] || r >= R) return;   // offsets[0] > 0 only for an appending call
   const long long t = row_src[r] / k;
   const u32x4* src = X + t * nvec;
   u32x4* dst = Xp + r * nvec;
@@ -251,10 +254,11 @@ extern "C" size_t feplb_permute_workspace_bytes(int32_t T, int32_t k, int32_t E,
   return layout((long long)T * k, E, G).bytes;
 }
 
-extern "C" int32_t feplb_permute(const int32_t* topk_ids, int32_t T, int32_t k, int32_t E,
-                                 const feplb_group* groups, int32_t G, const void* X, int32_t d,
-                                 void* Xp, int32_t R_cap, int32_t* offsets, int32_t* row_src,
-                                 int32_t* inv, void* ws, size_t ws_bytes, void* stream) {
+namespace {
+int32_t permute_impl(const int32_t* topk_ids, int32_t T, int32_t k, int32_t E,
+                     const feplb_group* groups, int32_t G, const void* X, int32_t d,
+                     void* Xp, int32_t R_cap, int32_t* offsets, int32_t* row_src,
+                     int32_t* inv, void* ws, size_t ws_bytes, void* stream, int append) {
   FEPLB_REQUIRE(T >= 0 && k >= 1 && E >= 1 && G >= 0 && R_cap >= 0 && d >= 0, FEPLB_EINVAL,
                 "permute: negative size");
   FEPLB_REQUIRE(E <= FEPLB_MAX_EXPERTS && G <= FEPLB_MAX_GROUPS && k <= FEPLB_MAX_TOPK,
@@ -305,12 +309,12 @@ extern "C" int32_t feplb_permute(const int32_t* topk_ids, int32_t T, int32_t k, 
                      L.nchunks, total);
   FEPLB_LAUNCH_CHECK("chunk_scan_kernel");
   hipLaunchKernelGGL(group_offsets_kernel, dim3(1), dim3(FEPLB_MAX_GROUPS), 0, s, tab, G, E, total,
-                     offsets, meta);
+                     offsets, meta, append);
   FEPLB_LAUNCH_CHECK("group_offsets_kernel");
   if (L.nchunks > 0) {
     const size_t lds = ((size_t)WAVES * E + E + 4 * (size_t)G) * sizeof(int);
     hipLaunchKernelGGL(assign_rows_kernel, dim3(cblocks), dim3(BLOCK), lds, s, topk_ids, A, E, G,
-                       L.nchunks, L.chunk, hist, meta, R_cap, row_src, inv);
+                       L.nchunks, L.chunk, hist, meta, R_cap, row_src, inv, append);
     FEPLB_LAUNCH_CHECK("assign_rows_kernel");
   }
   if (X && Xp && R_cap > 0 && d > 0) {
@@ -321,3 +325,22 @@ extern "C" int32_t feplb_permute(const int32_t* topk_ids, int32_t T, int32_t k, 
   }
   return FEPLB_OK;
 }
+}  // namespace
+
+extern "C" int32_t feplb_permute(const int32_t* topk_ids, int32_t T, int32_t k, int32_t E,
+                                 const feplb_group* groups, int32_t G, const void* X, int32_t d,
+                                 void* Xp, int32_t R_cap, int32_t* offsets, int32_t* row_src,
+                                 int32_t* inv, void* ws, size_t ws_bytes, void* stream) {
+  return permute_impl(topk_ids, T, k, E, groups, G, X, d, Xp, R_cap, offsets, row_src, inv, ws,
+                      ws_bytes, stream, 0);
+}
+
+extern "C" int32_t feplb_permute_append(const int32_t* topk_ids, int32_t T, int32_t k, int32_t E,
+                                        const feplb_group* groups, int32_t G, const void* X,
+                                        int32_t d, void* Xp, int32_t R_cap, int32_t* offsets,
+                                        int32_t* row_src, int32_t* inv, void* ws, size_t ws_bytes,
+                                        void* stream) {
+  return permute_impl(topk_ids, T, k, E, groups, G, X, d, Xp, R_cap, offsets, row_src, inv, ws,
+                      ws_bytes, stream, 1);
+}
+

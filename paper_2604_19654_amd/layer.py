@@ -85,15 +85,15 @@ class RankLayer:
         s = self.buf.slots[i]
         return s[: d * f].view(d, f), s[d * f: 2 * d * f].view(d, f), s[2 * d * f:].view(f, d)
 
-    def _permute(self, groups, X):
+    def _permute(self, groups, X, first=0, stream=None):
+        """Groups first .. first+len(groups)-1 of the layer's group table.  first > 0 appends to an
+        earlier call (rows continue at offsets[first])."""
         b = self.buf
         G = len(groups)
-        if self.fused_gather:   # indices only
-            B.feplb_permute(b.topk_ids, self.E, groups, None, self.R_cap, None, b.offsets[: G + 1], b.row_src,
-                            b.inv, b.ws_permute)
-        else:
-            B.feplb_permute(b.topk_ids, self.E, groups, X, self.R_cap, b.Xp, b.offsets[: G + 1], b.row_src,
-                            b.inv, b.ws_permute)
+        off = b.offsets[first: first + G + 1]
+        Xin, Xp = (None, None) if self.fused_gather else (X, b.Xp)   # fused: indices only
+        B.feplb_permute(b.topk_ids, self.E, groups, Xin, self.R_cap, Xp, off, b.row_src, b.inv, b.ws_permute,
+                        stream=stream, append=first > 0)
 
     def _ffn_range(self, X, g0, g1, wg, wu, wd, tag, mark):
         """One ragged launch per GEMM for groups [g0, g1).  With mark=True the
@@ -130,6 +130,68 @@ class RankLayer:
         return b.Y
 
     # -- rebalanced layer: static experts + replicas of the hottest foreign experts
+    def forward_rebalanced_early_static(self, logits, X, P, owner, dyn_flag, slots, this_rank,
+                                        static_weights: Dict[int, Tuple],
+                                        remote_sources: Dict[int, torch.Tensor], mark=False):
+        """Section 2.3 timeline in full: the static experts (this rank's own, known without the
+        plan) are permuted and their FFN is launched right after the router; the host meanwhile
+        reads the counts back on the side stream, plans, stages the replicas' weights and appends
+        the replicas' groups to the permutation, all behind the static FFN.  `this_rank` must be
+        the rank the plan will pick (the caller knows its own rank).  Returns (Y, info)."""
+        b = self.buf
+        main, side = torch.cuda.current_stream(), self.side_stream
+        if side is None or this_rank < 0:
+            raise B.FeplbError("early static launch needs staging slots and a known rank")
+        per = self.E // P
+        static = list(range(this_rank * per, (this_rank + 1) * per))
+        Gs = len(static)
+        self._mark("start", mark)
+        B.feplb_route_topk(logits, self.k, b.topk_ids, b.topk_w, b.counts)
+        self._mark("routed", mark)
+        routed = self.timeline.setdefault("_routed", B.HipEvent())
+        routed.record(main)
+        # static range: needs nothing from the host
+        self._permute([(e, 0, B.ORD_MAX) for e in static], X)
+        self._mark("permuted", mark)
+        permuted = self.timeline.setdefault("_permuted", B.HipEvent())
+        permuted.record(main)
+        wstat = [static_weights[e] for e in static]
+        slots_w = [self.slot_views(i) for i in range(self.n_slots)]
+        wg, wu, wd = ([w[i] for w in wstat + slots_w] for i in range(3))
+        self._ffn_range(X, 0, Gs, wg, wu, wd, "static", mark)
+        # meanwhile: counts to the host on the side stream (waits for the router only), plan
+        B.feplb_stream_wait(side, routed)
+        with torch.cuda.stream(side):
+            b.counts_host.copy_(b.counts, non_blocking=True)
+        side.synchronize()
+        n = b.counts_host.numpy().astype(np.int64)
+        moves, before, after, rank = B.feplb_plan(P, owner, n, dyn_flag, slots, 0, B.PLAN_OVERFLOW, this_rank)
+        if rank != this_rank:
+            raise B.FeplbError("the plan picked another receiving rank than the one given")
+        if len(moves) > self.n_slots:
+            raise B.FeplbError("more replicas than staging slots")
+        groups = [(e, 0, B.ORD_MAX) for e in static] + [(e, lo, lo + rows) for (e, _src, _dst, rows, lo) in moves]
+        G = len(groups)
+        # replicas: weights by the copy engine, their rows appended to the permutation, both on the
+        # side stream behind the static FFN (the append shares the permute workspace and buffers
+        # with the static call, hence the wait for it)
+        if mark and moves:
+            self.timeline.setdefault("copy_start", B.HipEvent()).record(side)
+        for i, (e, *_rest) in enumerate(moves):
+            B.feplb_stage_weights(b.slots[i], remote_sources[e], side, None)
+        if moves:
+            B.feplb_stream_wait(side, permuted)
+            self._permute(groups[Gs:], X, first=Gs, stream=side)
+            self.staged.record(side)
+            B.feplb_stream_wait(main, self.staged)
+            self._mark("staged", mark)
+            self._ffn_range(X, Gs, G, wg, wu, wd, "dynamic", mark)
+        self._mark("dynamic_done", mark)
+        B.feplb_unpermute_combine(b.Yp, b.inv, b.topk_w, self.T, self.k, self.d, b.Y)
+        self._mark("combined", mark)
+        info = dict(rank=rank, moves=moves, groups=groups, load_before=before, load_after=after, n=n)
+        return b.Y, info
+
     def forward_rebalanced(self, logits, X, P, owner, dyn_flag, slots, this_rank,
                            static_weights: Dict[int, Tuple], remote_sources: Dict[int, torch.Tensor],
                            mark=False, overlap=True):

@@ -83,13 +83,19 @@ def prepare(name: str, device="cuda:0", yp_dtype=torch.float32, source_kind="dev
                     moves, source_kind)
 
 
-def step(p: Prepared, mark=False, overlap=True):
-    """One pass of the whole hot path over the workload's batch. Returns Y (bf16 [T,d])."""
+def step(p: Prepared, mark=False, overlap=True, early_static=True):
+    """One pass of the whole hot path over the workload's batch. Returns Y (bf16 [T,d]).
+    Rebalanced share: early_static launches the static experts' permute and FFN before the host
+    has the plan (needs overlap); otherwise the plan comes first and one permute covers all groups."""
     wl = p.wl
     if not p.rebalanced:
         return p.layer.forward(wl.logits, wl.X, p.groups, p.weights, mark=mark)
-    Y, info = p.layer.forward_rebalanced(wl.logits, wl.X, wl.P, wl.owner(), p.dyn_flag, p.slots, p.rank,
-                                         p.static_weights, p.remote_sources, mark=mark, overlap=overlap)
+    if early_static and overlap:
+        Y, info = p.layer.forward_rebalanced_early_static(wl.logits, wl.X, wl.P, wl.owner(), p.dyn_flag, p.slots,
+                                                          p.rank, p.static_weights, p.remote_sources, mark=mark)
+    else:
+        Y, info = p.layer.forward_rebalanced(wl.logits, wl.X, wl.P, wl.owner(), p.dyn_flag, p.slots, p.rank,
+                                             p.static_weights, p.remote_sources, mark=mark, overlap=overlap)
     p.moves = info["moves"]
     p.groups = info["groups"]
     return Y

@@ -108,6 +108,36 @@ def test_permute_parity(T, E, k, d, skew, seed):
         assert torch.equal(Xp.cpu()[:R], want)            # byte copy: bit-exact
 
 
+def test_permute_in_two_calls_equals_one_call():
+    # static groups first, replicas appended later (Section 2.3 timeline): same offsets, row_src, inv, Xp
+    T, E, k, d = 3000, 64, 4, 128
+    g = torch.Generator().manual_seed(5)
+    ids = torch.stack([torch.randperm(E, generator=g)[:k] for _ in range(T)]).to(torch.int32).to(DEV)
+    X = torch.randn((T, d), generator=g).to(torch.bfloat16).to(DEV)
+    first = [(e, 0, fe.ORD_MAX) for e in range(8)]
+    later = [(40, 0, 50), (41, 10, 10), (9, 0, fe.ORD_MAX), (40, 50, 120), (63, 5, fe.ORD_MAX)]
+    R_cap = T * k
+    Xp1, off1, src1, inv1 = fe.feplb_permute(ids, E, first + later, X, R_cap)
+    Xp2 = torch.zeros_like(Xp1)
+    off2 = torch.zeros_like(off1)
+    src2 = torch.full_like(src1, -5)
+    inv2 = torch.full_like(inv1, -9)
+    fe.feplb_permute(ids, E, first, X, R_cap, Xp2, off2[: len(first) + 1], src2, inv2)
+    fe.feplb_permute(ids, E, later, X, R_cap, Xp2, off2[len(first):], src2, inv2, append=True)
+    torch.cuda.synchronize()
+    R = int(off1[-1])
+    assert torch.equal(off1, off2) and torch.equal(inv1, inv2)
+    assert torch.equal(src1[:R], src2[:R]) and torch.equal(Xp1[:R], Xp2[:R])
+    o_off, o_src, o_inv = orc.permute(ids.cpu().numpy(), first + later)
+    assert np.array_equal(off2.cpu().numpy(), o_off) and np.array_equal(inv2.cpu().numpy(), o_inv)
+    # index-only append (the GEMM gathers the rows)
+    off3 = torch.zeros_like(off1); src3 = torch.full_like(src1, -5); inv3 = torch.full_like(inv1, -9)
+    fe.feplb_permute(ids, E, first, None, R_cap, None, off3[: len(first) + 1], src3, inv3)
+    fe.feplb_permute(ids, E, later, None, R_cap, None, off3[len(first):], src3, inv3, append=True)
+    torch.cuda.synchronize()
+    assert torch.equal(off1, off3) and torch.equal(inv1, inv3) and torch.equal(src1[:R], src3[:R])
+
+
 def test_permute_degenerate_cases():
     ids = torch.from_numpy(random_ids(64, 8, 2, 9)[0]).to(DEV)
     X = torch.ones((64, 16), dtype=torch.bfloat16, device=DEV)
@@ -349,11 +379,19 @@ def test_rebalanced_layer_parity_reduced(source_kind, fused_gather):
     torch.cuda.synchronize()
     assert len(p.moves) == 4 and sum(m[3] for m in p.moves) > 0
     oracle_layer(p, Y)
-    # the side-stream copy and the same copy issued in stream order give the same bytes
+    # the side-stream copy and the same copy issued in stream order give the same bytes, and so
+    # does planning first instead of launching the static experts before the plan is known
     Y1 = Y.clone()
     Y2 = runner.step(p, overlap=False)
     torch.cuda.synchronize()
     assert torch.equal(Y1, Y2)
+    Y3 = runner.step(p, early_static=False)
+    torch.cuda.synchronize()
+    assert torch.equal(Y1, Y3)
+    for _ in range(3):   # repeated steps reuse slots, events and the permute workspace
+        Y4 = runner.step(p)
+    torch.cuda.synchronize()
+    assert torch.equal(Y1, Y4)
 
 
 def test_output_does_not_depend_on_where_an_experts_rows_run():
