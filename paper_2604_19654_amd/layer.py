@@ -68,8 +68,10 @@ class RankLayer:
             ws_ffn=torch.empty((B.feplb_grouped_ffn_workspace_bytes(R_cap, G_cap),), dtype=torch.uint8, device=dev),
             slots=torch.empty((n_slots, self.expert_elems), **bf) if n_slots else None,
         )
-        self.side_stream = torch.cuda.Stream(device=dev) if n_slots else None
+        self.side_stream = torch.cuda.Stream(device=dev) if n_slots else None      # staging copies
+        self.append_stream = torch.cuda.Stream(device=dev) if n_slots else None    # late permute of the replicas
         self.staged = B.HipEvent() if n_slots else None
+        self.appended = B.HipEvent() if n_slots else None
         self.timeline: Dict[str, B.HipEvent] = {}
 
     # -- helpers ---------------------------------------------------------
@@ -172,18 +174,23 @@ class RankLayer:
             raise B.FeplbError("more replicas than staging slots")
         groups = [(e, 0, B.ORD_MAX) for e in static] + [(e, lo, lo + rows) for (e, _src, _dst, rows, lo) in moves]
         G = len(groups)
-        # replicas: weights by the copy engine, their rows appended to the permutation, both on the
-        # side stream behind the static FFN (the append shares the permute workspace and buffers
-        # with the static call, hence the wait for it)
-        if mark and moves:
-            self.timeline.setdefault("copy_start", B.HipEvent()).record(side)
-        for i, (e, *_rest) in enumerate(moves):
-            B.feplb_stage_weights(b.slots[i], remote_sources[e], side, None)
+        # replicas: weights by the copy engine on the side stream, their rows appended to the
+        # permutation, both behind the static FFN (the append shares the permute workspace and
+        # buffers with the static call, hence the wait for it)
         if moves:
-            B.feplb_stream_wait(side, permuted)
-            self._permute(groups[Gs:], X, first=Gs, stream=side)
+            if mark:
+                self.timeline.setdefault("copy_start", B.HipEvent()).record(side)
+            for i, (e, *_rest) in enumerate(moves):
+                B.feplb_stage_weights(b.slots[i], remote_sources[e], side, None)
             self.staged.record(side)
+            # the append on a stream of its own: its small kernels wait for compute units the
+            # static GEMM holds, and the copies must not queue behind them
+            aux = self.append_stream
+            B.feplb_stream_wait(aux, permuted)
+            self._permute(groups[Gs:], X, first=Gs, stream=aux)
+            self.appended.record(aux)
             B.feplb_stream_wait(main, self.staged)
+            B.feplb_stream_wait(main, self.appended)
             self._mark("staged", mark)
             self._ffn_range(X, Gs, G, wg, wu, wd, "dynamic", mark)
         self._mark("dynamic_done", mark)
