@@ -3,7 +3,8 @@
 // expert's batch size and it must not fragment into per-expert launches).
 //
 // Two GEMM kernels, each ONE launch for a whole range of groups:
-//   gate_up : H[r,:]  = bf16( silu(Xp[r,:] Wg[g]) * (Xp[r,:] Wu[g]) )
+//   gate_up : H[r,:]  = bf16( silu(x_r Wg[g]) * (x_r Wu[g]) ),  x_r = Xp[r,:] or, with row_src,
+//             the token row X[row_src[r] / k, :] gathered while it is loaded
 //   down    : Yp[r,:] = H[r,:] Wd[g]
 // A small schedule kernel turns offsets[] (device memory, ragged, possibly
 // empty groups) into a table of row tiles; the GEMM grid covers an upper bound
@@ -13,16 +14,19 @@
 // (2 x 2), one per SIMD, each 128 x 128 as 4 x 4 MFMA 32x32x16 bf16 tiles
 // (256 fp32 accumulators per lane).  For gate_up the 256 weight columns are
 // 128 gate + the matching 128 up columns, so the SwiGLU product happens in
-// registers and only H is written.  LDS holds four stages of (A 256 rows x 32 k,
-// k-contiguous; B 32 k x 256 columns, column-contiguous as in memory), filled
-// by LDS-DMA loads (global_load_lds_dwordx4: HBM/L2 -> LDS without passing
-// through registers) with XOR-swizzled layouts instead of padding; a tile is
-// requested three steps before its use, one barrier per step.
+// registers and only H is written.  LDS (all 160 KB of a CU) holds six stages of A
+// (256 rows x 32 k, k-contiguous) and four of B (32 k x 256 columns, column-contiguous as
+// in memory), filled by LDS-DMA loads (global_load_lds_dwordx4: HBM/L2 -> LDS without
+// passing through registers) with XOR-swizzled layouts instead of padding; one barrier
+// per step; A tiles are requested in pairs that share 128-byte memory lines.
 // Weights are row-major [K,N] (N contiguous) as the caller stores them, while
 // an MFMA lane needs 8 consecutive k of one column: the B fragments are read
 // with the transposing LDS load of gfx950 (ds_read_b64_tr_b16), which hands
 // lane i of a 16-lane group the 4 k-values of column i from a 4(k) x 16(n)
 // block, so no transpose is done in registers.
+// The MFMAs take the weights as their first operand, so a lane ends up with one token row and
+// runs of four consecutive output columns; the epilogue passes them through LDS once more so
+// that every store instruction writes whole 128-byte lines.
 // Blocks are mapped to tiles in 8 x 4 patches per XCD (workgroups are dealt
 // round-robin to the 8 XCDs, each with its own L2), so the 32 tiles an XCD
 // runs at a time share 8 row panels and 4 weight panels.
