@@ -237,6 +237,46 @@ def test_grouped_ffn_short_tail_tiles_repeatable(d, f, sizes):
     assert eh <= 1.0 and ey.max() <= ROW_TOL
 
 
+def test_grouped_ffn_repeatable_over_random_shapes():
+    # a property that holds at any size: the hand-scheduled load pipeline has no timing-dependent
+    # result.  Random widths (all loop shapes: whole trips of the stage ring plus 0, 4 or 8 steps)
+    # and ragged group patterns; three launches each must give the same bytes, rows past R untouched.
+    rng = np.random.default_rng(123)
+    for trial in range(40):
+        d = int(rng.choice([256, 512, 768, 1024, 2048, 4096]))
+        f = int(rng.choice([128, 256, 384, 512, 1024, 1536]))
+        G = int(rng.integers(1, 20))
+        kind = int(rng.integers(0, 3))
+        if kind == 0:
+            sizes = rng.integers(0, 6, size=G)
+        elif kind == 1:
+            sizes = rng.integers(250, 262, size=G)
+        else:
+            sizes = rng.choice([0, 1, 4, 255, 256, 257, 260, 511, 516, 1024, 1030, 4100], size=G)
+        sizes = [int(x) for x in sizes]
+        R = sum(sizes)
+        if R == 0:
+            continue
+        offsets = torch.tensor(np.concatenate([[0], np.cumsum(sizes)]), dtype=torch.int32, device=DEV)
+        g = torch.Generator(device=DEV)
+        g.manual_seed(trial)
+        Xp = torch.empty((R + 3, d), device=DEV).normal_(generator=g).to(torch.bfloat16)
+        W = [tuple(torch.empty(sh, device=DEV).normal_(generator=g).mul_(0.05).to(torch.bfloat16)
+                   for sh in ((d, f), (d, f), (f, d))) for _ in range(G)]
+        cols = [[w[i] for w in W] for i in range(3)]
+        first = None
+        for rep in range(3):
+            H = torch.full((R + 3, f), 3.0, dtype=torch.bfloat16, device=DEV)
+            Yp = torch.full((R + 3, d), 3.0, device=DEV)
+            fe.feplb_grouped_ffn(Xp, offsets, 0, G, d, f, *cols, H, Yp)
+            torch.cuda.synchronize()
+            assert (H[R:].float() == 3.0).all() and (Yp[R:] == 3.0).all()
+            if first is None:
+                first = (H, Yp)
+            else:
+                assert torch.equal(first[0], H) and torch.equal(first[1], Yp), f"trial {trial} d={d} f={f} sizes={sizes}"
+
+
 def test_grouped_ffn_gathering_rows_equals_reading_the_permuted_copy():
     # row_src given: row r of the input is X[row_src[r] // k]; the bytes must equal a run on the
     # materialised copy (the same MFMAs on the same operands)
