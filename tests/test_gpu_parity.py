@@ -301,6 +301,34 @@ def test_grouped_ffn_gathering_rows_equals_reading_the_permuted_copy():
         fe.feplb_grouped_ffn(X, offsets, 0, G, d, f, *cols, H2, Y2, row_src=flat, k=0)
 
 
+def test_grouped_ffn_phases_one_by_one_equal_one_call_and_capacity_truncates():
+    # the benchmark issues SCHEDULE, GATE_UP and DOWN as separate calls (to bracket each GEMM with
+    # events); the bytes must equal the single FFN_ALL call.  Then a capacity below the row count:
+    # rows past R_cap are neither read nor written.
+    sizes = [300, 0, 129, 513]
+    d, f, G = 512, 256, 4
+    offsets = torch.tensor(np.concatenate([[0], np.cumsum(sizes)]), dtype=torch.int32, device=DEV)
+    R = int(sum(sizes))
+    Xp = torch.randn((R, d), generator=torch.Generator().manual_seed(13)).to(torch.bfloat16).to(DEV)
+    W = [tuple(m.to(DEV) for m in w) for w in make_weights(G, d, f, 15)]
+    cols = [[w[i] for w in W] for i in range(3)]
+    H1 = torch.zeros((R, f), dtype=torch.bfloat16, device=DEV); Y1 = torch.zeros((R, d), device=DEV)
+    H2 = torch.zeros_like(H1); Y2 = torch.zeros_like(Y1)
+    ws = torch.empty((fe.feplb_grouped_ffn_workspace_bytes(R, G),), dtype=torch.uint8, device=DEV)
+    fe.feplb_grouped_ffn(Xp, offsets, 0, G, d, f, *cols, H1, Y1)
+    for ph in (fe.FFN_SCHEDULE, fe.FFN_GATE_UP, fe.FFN_DOWN):
+        fe.feplb_grouped_ffn(Xp, offsets, 0, G, d, f, *cols, H2, Y2, phases=ph, ws=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(H1, H2) and torch.equal(Y1, Y2)
+    cap = 700   # inside the last group
+    H3 = torch.full((cap + 5, f), 7.0, dtype=torch.bfloat16, device=DEV)[:cap]
+    Y3 = torch.full((cap + 5, d), 7.0, device=DEV)[:cap]
+    fe.feplb_grouped_ffn(Xp[:cap].contiguous(), offsets, 0, G, d, f, *cols, H3, Y3)
+    torch.cuda.synchronize()
+    assert torch.equal(H3, H1[:cap]) and torch.equal(Y3, Y1[:cap])
+    assert (H3._base[cap:].float() == 7.0).all() and (Y3._base[cap:] == 7.0).all()
+
+
 def test_grouped_ffn_range_split_equals_one_call():
     # static range then dynamic range (two launches) gives the same bytes as one launch
     sizes = [200, 3, 0, 150, 90]
