@@ -19,6 +19,9 @@ What each function follows:
                     Section 2.3 (static / dynamic expert partition).
   ffn_rows, grouped_ffn   Section 3.1 (expert compute is a grouped GEMM);
                     the expert is a SwiGLU MLP without biases.
+  ffn_rows_backward, grouped_ffn_backward   the gradients of that definition
+                    (Section 3.2 reports the layer's backward time beside the
+                    forward one): chain rule on y = (silu(x Wg) * (x Wu)) Wd.
   combine           Section 2.3 (combine returns expert outputs to tokens).
   moe_token, moe_tokens   the layer's definition per token, no permutation.
   plan_whole        Section 2.3, the greedy whole-expert balancer.
@@ -138,6 +141,48 @@ def grouped_ffn(Xp: np.ndarray, offsets: np.ndarray, weights):
         if hi > lo:
             H[lo:hi], Yp[lo:hi] = ffn_rows(Xp[lo:hi], *weights[g])
     return H, Yp
+
+
+def ffn_rows_backward(x, w_gate, w_up, w_down, dy):
+    """Gradients of L = sum(y * dy) for y = ffn_rows(x, Wg, Wu, Wd)[1], by the
+    chain rule in float64.  With a = x Wg, b = x Wu, s = sigmoid(a):
+      dh = dy Wd^T;   db = dh * a * s;   da = dh * b * s * (1 + a (1 - s));
+      dx = da Wg^T + db Wu^T;   dWg = x^T da;   dWu = x^T db;   dWd = h^T dy.
+    Returns (dx [m,d], dWg [d,f], dWu [d,f], dWd [f,d])."""
+    x = np.asarray(x, dtype=np.float64)
+    wg = np.asarray(w_gate, dtype=np.float64)
+    wu = np.asarray(w_up, dtype=np.float64)
+    wd = np.asarray(w_down, dtype=np.float64)
+    dy = np.asarray(dy, dtype=np.float64)
+    a = x @ wg
+    b = x @ wu
+    s = 1.0 / (1.0 + np.exp(-a))
+    h = a * s * b
+    dh = dy @ wd.T
+    db = dh * a * s
+    da = dh * b * s * (1.0 + a * (1.0 - s))
+    dx = da @ wg.T + db @ wu.T
+    return dx, x.T @ da, x.T @ db, h.T @ dy
+
+
+def grouped_ffn_backward(Xp, offsets, weights, dYp):
+    """Per group g, ffn_rows_backward on rows offsets[g]..offsets[g+1] with the
+    group's own matrices.  A group without rows has zero weight gradients.
+    Returns (dXp [R,d], [(dWg, dWu, dWd) per group])."""
+    R = int(offsets[-1])
+    d = Xp.shape[1]
+    dXp = np.zeros((R, d))
+    grads = []
+    for g in range(len(weights)):
+        lo, hi = int(offsets[g]), int(offsets[g + 1])
+        wg, wu, wd = weights[g]
+        if hi > lo:
+            dx, dwg, dwu, dwd = ffn_rows_backward(Xp[lo:hi], wg, wu, wd, dYp[lo:hi])
+            dXp[lo:hi] = dx
+            grads.append((dwg, dwu, dwd))
+        else:
+            grads.append((np.zeros(wg.shape), np.zeros(wu.shape), np.zeros(wd.shape)))
+    return dXp, grads
 
 
 # --------------------------------------------------------------------------

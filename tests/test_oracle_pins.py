@@ -318,6 +318,113 @@ def test_grouped_ffn_uses_each_groups_own_weights_and_skips_empty():
             assert np.allclose(H[lo:hi], bh, atol=1e-12) and np.allclose(Yp[lo:hi], by, atol=1e-12)
 
 
+# ---------------------------------------------------------------- expert FFN, backward
+def test_ffn_backward_matches_central_differences_of_the_forward():
+    # the gradient of L = sum(y * dy) with respect to every input, from the forward definition alone
+    rng = np.random.default_rng(10)
+    m, d, f = 3, 5, 4                      # d != f so a transposed operand cannot even multiply
+    x, wg, wu, wd, dy = (rng.normal(size=s) for s in ((m, d), (d, f), (d, f), (f, d), (m, d)))
+    got = orc.ffn_rows_backward(x, wg, wu, wd, dy)
+
+    def loss(x_, wg_, wu_, wd_):
+        return float(np.sum(orc.ffn_rows(x_, wg_, wu_, wd_)[1] * dy))
+
+    args = [x, wg, wu, wd]
+    eps = 1e-5
+    for which in range(4):
+        num = np.zeros_like(args[which])
+        for idx in np.ndindex(*args[which].shape):
+            hi = [a.copy() for a in args]
+            lo = [a.copy() for a in args]
+            hi[which][idx] += eps
+            lo[which][idx] -= eps
+            num[idx] = (loss(*hi) - loss(*lo)) / (2 * eps)
+        assert np.allclose(got[which], num, rtol=1e-7, atol=1e-8), which
+
+
+def test_ffn_backward_torch_autograd_special_case():
+    rng = np.random.default_rng(11)
+    m, d, f = 17, 24, 10
+    x, wg, wu, wd, dy = (rng.normal(size=s) for s in ((m, d), (d, f), (d, f), (f, d), (m, d)))
+    tx, tg, tu, td = (torch.from_numpy(v).requires_grad_(True) for v in (x, wg, wu, wd))
+    y = (torch.nn.functional.silu(tx @ tg) * (tx @ tu)) @ td
+    y.backward(torch.from_numpy(dy))
+    got = orc.ffn_rows_backward(x, wg, wu, wd, dy)
+    for g, t in zip(got, (tx, tg, tu, td)):
+        assert np.allclose(g, t.grad.numpy(), rtol=1e-11, atol=1e-11)
+
+
+def test_ffn_backward_single_entry_closed_form():
+    # one path through the expert: y_3 = silu(x_0) * x_2, so every gradient is a scalar formula
+    d = f = 4
+    x = np.array([[0.5, -1.0, 2.0, 3.0]])
+    wg = np.zeros((d, f)); wg[0, 1] = 1.0
+    wu = np.zeros((d, f)); wu[2, 1] = 1.0
+    wd = np.zeros((f, d)); wd[1, 3] = 1.0
+    dy = np.array([[7.0, 0.0, 0.0, 1.5]])          # only dy_3 can matter
+    a, b = 0.5, 2.0
+    sg = 1.0 / (1.0 + math.exp(-a))
+    dsilu = sg * (1.0 + a * (1.0 - sg))
+    dx, dwg, dwu, dwd = orc.ffn_rows_backward(x, wg, wu, wd, dy)
+    want_dx = np.zeros((1, d)); want_dx[0, 0] = 1.5 * b * dsilu; want_dx[0, 2] = 1.5 * silu(a)
+    assert np.allclose(dx, want_dx, atol=1e-15)
+    # dWg[i,1] = x_i * da_1, dWu[i,1] = x_i * db_1, dWd[1,i] = h_1 * dy_i; everything else zero
+    want = np.zeros((d, f)); want[:, 1] = x[0] * (1.5 * b * dsilu)
+    assert np.allclose(dwg, want, atol=1e-15)
+    want = np.zeros((d, f)); want[:, 1] = x[0] * (1.5 * silu(a))
+    assert np.allclose(dwu, want, atol=1e-15)
+    want = np.zeros((f, d)); want[1, :] = silu(a) * b * dy[0]
+    assert np.allclose(dwd, want, atol=1e-15)
+
+
+def test_ffn_backward_is_linear_in_dy_and_sums_weight_gradients_over_rows():
+    rng = np.random.default_rng(12)
+    m, d, f = 6, 8, 5
+    x, wg, wu, wd, dy1, dy2 = (rng.normal(size=s) for s in ((m, d), (d, f), (d, f), (f, d), (m, d), (m, d)))
+    g1 = orc.ffn_rows_backward(x, wg, wu, wd, dy1)
+    g2 = orc.ffn_rows_backward(x, wg, wu, wd, dy2)
+    g12 = orc.ffn_rows_backward(x, wg, wu, wd, 2.0 * dy1 - 3.0 * dy2)
+    for a, b, c in zip(g1, g2, g12):
+        assert np.allclose(c, 2.0 * a - 3.0 * b, atol=1e-11)
+    # rows are independent: dx row by row, weight gradients are the sum over the rows
+    parts = [orc.ffn_rows_backward(x[r:r + 1], wg, wu, wd, dy1[r:r + 1]) for r in range(m)]
+    assert np.allclose(np.concatenate([p_[0] for p_ in parts]), g1[0], atol=1e-12)
+    for i in (1, 2, 3):
+        assert np.allclose(sum(p_[i] for p_ in parts), g1[i], atol=1e-11)
+    assert all(np.all(v == 0) for v in orc.ffn_rows_backward(x, wg, wu, wd, np.zeros((m, d))))
+
+
+def test_grouped_ffn_backward_uses_each_groups_own_rows_and_weights():
+    rng = np.random.default_rng(13)
+    d, f = 6, 4
+    offsets = np.array([0, 3, 3, 7], dtype=np.int32)          # middle group empty
+    Xp, dYp = rng.normal(size=(7, d)), rng.normal(size=(7, d))
+    ws = [tuple(rng.normal(size=s) for s in ((d, f), (d, f), (f, d))) for _ in range(3)]
+    dXp, grads = orc.grouped_ffn_backward(Xp, offsets, ws, dYp)
+    for g, (lo, hi) in enumerate([(0, 3), (3, 3), (3, 7)]):
+        if hi > lo:
+            want = orc.ffn_rows_backward(Xp[lo:hi], *ws[g], dYp[lo:hi])
+            assert np.array_equal(dXp[lo:hi], want[0])
+            assert all(np.array_equal(a, b) for a, b in zip(grads[g], want[1:]))
+        else:
+            assert all(np.all(v == 0) for v in grads[g])
+            assert [v.shape for v in grads[g]] == [(d, f), (d, f), (f, d)]
+    # the whole-batch loss differentiated numerically through grouped_ffn, a few coordinates
+    def loss(Xq, wsq):
+        return float(np.sum(orc.grouped_ffn(Xq, offsets, wsq)[1] * dYp))
+    eps = 1e-5
+    for (r, c) in [(0, 0), (4, 5), (6, 2)]:
+        hi_, lo_ = Xp.copy(), Xp.copy()
+        hi_[r, c] += eps; lo_[r, c] -= eps
+        assert abs((loss(hi_, ws) - loss(lo_, ws)) / (2 * eps) - dXp[r, c]) < 1e-7
+    for (g, which, idx) in [(0, 0, (1, 2)), (2, 1, (5, 3)), (2, 2, (3, 4)), (1, 0, (0, 0))]:
+        hi_ = [list(w) for w in ws]; lo_ = [list(w) for w in ws]
+        hi_[g][which] = hi_[g][which].copy(); lo_[g][which] = lo_[g][which].copy()
+        hi_[g][which][idx] += eps; lo_[g][which][idx] -= eps
+        num = (loss(Xp, hi_) - loss(Xp, lo_)) / (2 * eps)
+        assert abs(num - grads[g][which][idx]) < 1e-7
+
+
 # ---------------------------------------------------------------- combine, end to end
 def small_layer(seed, T=40, E=8, k=2, d=12, f=10):
     rng = np.random.default_rng(seed)
