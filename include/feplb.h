@@ -181,6 +181,68 @@ int32_t feplb_grouped_ffn(const void* Xp, const int32_t* row_src, int32_t T, int
                           void* H, void* Yp, int32_t yp_dtype, int32_t phases,
                           void* ws, size_t ws_bytes, void* stream);
 
+/* ------------------------------------------------------------------ expert FFN, training
+ * Section 3.2 reports the MoE layer's time per forward AND backward pass; the
+ * backward of the Grouped GEMM of Section 3.1 is again grouped GEMMs over the same
+ * ragged groups.  For every row r of group g, with a, b, H as above, s = sigmoid(a)
+ * and the incoming gradient dYp[r,:]:
+ *     dH = dYp[r,:] * W_down[g]^T
+ *     da = dH * b * s * (1 + a (1 - s))      db = dH * a * s      (rounded to bf16)
+ *     dXp[r,:] = da * W_gate[g]^T + db * W_up[g]^T
+ *     dW_down[g] = sum_r H[r,:]^T dYp[r,:]   dW_gate[g] = sum_r Xp[r,:]^T da
+ *     dW_up[g]   = sum_r Xp[r,:]^T db        (fp32, overwritten; zero for an empty group)
+ *
+ * feplb_grouped_ffn_train is feplb_grouped_ffn that also keeps what the backward
+ * needs: AB, device bf16 [R_cap, 2f], receives a in columns [0,f) and b in [f,2f).
+ *
+ * feplb_grouped_ffn_backward:
+ *   Xp      device, bf16 [R_cap,d], the permuted rows (a materialised copy; no row_src here)
+ *   offsets, g_begin, g_end, R_cap, d, f, w_gate, w_up, w_down   as in the forward call
+ *   H       device, bf16 [R_cap,f]   as written by the forward call
+ *   AB      device, bf16 [R_cap,2f]  in: a | b from feplb_grouped_ffn_train; out: da | db
+ *   dYp     device, bf16 [R_cap,d]   gradient of the loss with respect to Yp
+ *   dXp     device, [R_cap,d] of dxp_dtype (FEPLB_F32 or FEPLB_BF16)  out
+ *   dw_gate, dw_up, dw_down  host arrays of (g_end) device pointers indexed by g:
+ *           fp32 [d,f], [d,f], [f,d]  out
+ *   WT      device scratch, feplb_grouped_ffn_backward_wt_bytes(g_end - g_begin, d, f)
+ *           bytes: receives the transposed weights (phase TRANSPOSE), read by DGRAD
+ *   phases  any non-empty subset of FEPLB_BWD_SCHEDULE (tile table from offsets[], as
+ *           in the forward call; may be skipped when ws still holds the forward call's
+ *           table for the same range), FEPLB_BWD_TRANSPOSE, FEPLB_BWD_DGRAD (needs
+ *           the table and WT), FEPLB_BWD_WGRAD.  WGRAD for the gate and up matrices
+ *           needs da | db, i.e. DGRAD in the same or an earlier call.
+ *   ws      device, feplb_grouped_ffn_workspace_bytes(R_cap, g_end - g_begin) bytes
+ * Rows past offsets[g_end] are neither read into any result nor written.
+ * Limits: d % 256 == 0, f % 256 == 0, g_end <= FEPLB_MAX_GROUPS, R_cap >= 32 for WGRAD.
+ */
+#define FEPLB_BWD_SCHEDULE 1
+#define FEPLB_BWD_TRANSPOSE 2
+#define FEPLB_BWD_DGRAD 4
+#define FEPLB_BWD_WGRAD 8
+#define FEPLB_BWD_ALL 15
+
+int32_t feplb_grouped_ffn_train(const void* Xp, const int32_t* row_src, int32_t T, int32_t k,
+                                const int32_t* offsets,
+                                int32_t g_begin, int32_t g_end, int32_t R_cap,
+                                int32_t d, int32_t f,
+                                const void* const* w_gate, const void* const* w_up,
+                                const void* const* w_down,
+                                void* H, void* AB, void* Yp, int32_t yp_dtype, int32_t phases,
+                                void* ws, size_t ws_bytes, void* stream);
+
+size_t feplb_grouped_ffn_backward_wt_bytes(int32_t n_groups, int32_t d, int32_t f);
+
+int32_t feplb_grouped_ffn_backward(const void* Xp, const int32_t* offsets,
+                                   int32_t g_begin, int32_t g_end, int32_t R_cap,
+                                   int32_t d, int32_t f,
+                                   const void* const* w_gate, const void* const* w_up,
+                                   const void* const* w_down,
+                                   const void* H, void* AB, const void* dYp,
+                                   void* dXp, int32_t dxp_dtype,
+                                   void* const* dw_gate, void* const* dw_up, void* const* dw_down,
+                                   void* WT, size_t wt_bytes, int32_t phases,
+                                   void* ws, size_t ws_bytes, void* stream);
+
 /* ------------------------------------------------------------------ combine
  * Section 2.3: "the Combine phase returns results to source devices"; this is
  * its local part: Y[t,:] = sum over slots j with inv[t*k+j] >= 0 of

@@ -19,6 +19,7 @@ ORD_MAX = 2**31 - 1
 MAX_GROUPS = 128   # FEPLB_MAX_GROUPS
 F32, BF16 = 0, 1
 FFN_GATE_UP, FFN_DOWN, FFN_SCHEDULE, FFN_ALL = 1, 2, 4, 7
+BWD_SCHEDULE, BWD_TRANSPOSE, BWD_DGRAD, BWD_WGRAD, BWD_ALL = 1, 2, 4, 8, 15
 PLAN_WHOLE, PLAN_OVERFLOW = 0, 1
 
 
@@ -62,6 +63,13 @@ def lib():
         L.feplb_grouped_ffn_workspace_bytes.restype = sz
         L.feplb_grouped_ffn.argtypes = [vp, vp, i32, i32, vp, i32, i32, i32, i32, i32, C.POINTER(vp), C.POINTER(vp),
                                         C.POINTER(vp), vp, vp, i32, i32, vp, sz, vp]
+        L.feplb_grouped_ffn_train.argtypes = [vp, vp, i32, i32, vp, i32, i32, i32, i32, i32, C.POINTER(vp), C.POINTER(vp),
+                                              C.POINTER(vp), vp, vp, vp, i32, i32, vp, sz, vp]
+        L.feplb_grouped_ffn_backward_wt_bytes.argtypes = [i32, i32, i32]
+        L.feplb_grouped_ffn_backward_wt_bytes.restype = sz
+        L.feplb_grouped_ffn_backward.argtypes = [vp, vp, i32, i32, i32, i32, i32, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
+                                                 vp, vp, vp, vp, i32, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
+                                                 vp, sz, i32, vp, sz, vp]
         L.feplb_unpermute_combine.argtypes = [vp, i32, vp, vp, i32, i32, i32, vp, vp]
         L.feplb_stage_weights.argtypes = [vp, vp, sz, vp, vp]
         L.feplb_stream_wait.argtypes = [vp, vp]
@@ -69,7 +77,8 @@ def lib():
         L.feplb_expert_bytes.restype = sz
         L.feplb_plan.argtypes = [i32, i32, vp, vp, vp, vp, i64, i32, i32, C.POINTER(Move), i32,
                                  C.POINTER(i32), vp, vp, C.POINTER(i32)]
-        for name in ("feplb_route_topk", "feplb_permute", "feplb_permute_append", "feplb_grouped_ffn", "feplb_unpermute_combine",
+        for name in ("feplb_route_topk", "feplb_permute", "feplb_permute_append", "feplb_grouped_ffn", "feplb_grouped_ffn_train",
+                     "feplb_grouped_ffn_backward", "feplb_unpermute_combine",
                      "feplb_stage_weights", "feplb_stream_wait", "feplb_plan"):
             getattr(L, name).restype = i32
         _LIB = L
@@ -235,11 +244,13 @@ def _ptr_array(tensors: Sequence[Optional[torch.Tensor]]):
 
 
 def feplb_grouped_ffn(Xp, offsets, g_begin, g_end, d, f, w_gate, w_up, w_down, H, Yp,
-                      phases=FFN_ALL, ws=None, stream=None, row_src=None, k=0):
+                      phases=FFN_ALL, ws=None, stream=None, row_src=None, k=0, AB=None):
     """Runs groups [g_begin, g_end).  w_* are sequences (indexed by group) of bf16
     tensors or raw device addresses.  H bf16 [R_cap,f]; Yp fp32 or bf16 [R_cap,d].
     With row_src (int32 [R_cap], from feplb_permute) and k, Xp is the unpermuted X [T,d] and the
-    rows X[row_src[r] // k] are gathered as the gate/up GEMM loads them."""
+    rows X[row_src[r] // k] are gathered as the gate/up GEMM loads them.
+    With AB (bf16 [R_cap,2f]) the call is feplb_grouped_ffn_train: the gate and up products are
+    kept in AB for feplb_grouped_ffn_backward."""
     R_cap = H.shape[0]
     yp_dtype = F32
     if Yp is not None:
@@ -248,11 +259,47 @@ def feplb_grouped_ffn(Xp, offsets, g_begin, g_end, d, f, w_gate, w_up, w_down, H
         ws = torch.empty((feplb_grouped_ffn_workspace_bytes(R_cap, g_end),), dtype=torch.uint8,
                          device=H.device)
     n_src = int(Xp.shape[0]) if row_src is not None else 0
+    if AB is not None:
+        _need(AB, torch.bfloat16, "AB")
+        if tuple(AB.shape) != (R_cap, 2 * f):
+            raise FeplbError("AB must be [R_cap, 2f]")
+        _check(lib().feplb_grouped_ffn_train(_ptr(Xp), _ptr(row_src), n_src, k, _ptr(offsets), g_begin, g_end, R_cap, d, f,
+                                             _ptr_array(w_gate), _ptr_array(w_up), _ptr_array(w_down),
+                                             _ptr(H), _ptr(AB), _ptr(Yp), yp_dtype, phases, _ptr(ws), ws.numel(),
+                                             _stream(stream)), "feplb_grouped_ffn_train")
+        return H, Yp
     _check(lib().feplb_grouped_ffn(_ptr(Xp), _ptr(row_src), n_src, k, _ptr(offsets), g_begin, g_end, R_cap, d, f,
                                    _ptr_array(w_gate), _ptr_array(w_up), _ptr_array(w_down),
                                    _ptr(H), _ptr(Yp), yp_dtype, phases, _ptr(ws), ws.numel(),
                                    _stream(stream)), "feplb_grouped_ffn")
     return H, Yp
+
+
+def feplb_grouped_ffn_backward_wt_bytes(n_groups, d, f) -> int:
+    return int(lib().feplb_grouped_ffn_backward_wt_bytes(n_groups, d, f))
+
+
+def feplb_grouped_ffn_backward(Xp, offsets, g_begin, g_end, d, f, w_gate, w_up, w_down, H, AB, dYp, dXp,
+                               dw_gate, dw_up, dw_down, WT=None, phases=BWD_ALL, ws=None, stream=None):
+    """Backward of groups [g_begin, g_end).  Xp bf16 [R_cap,d] (materialised), H bf16 [R_cap,f] and
+    AB bf16 [R_cap,2f] as left by feplb_grouped_ffn(..., AB=AB), dYp bf16 [R_cap,d].  Writes dXp
+    (fp32 or bf16 [R_cap,d]), da | db over AB, and the fp32 weight gradients dw_*[g]."""
+    R_cap = H.shape[0]
+    dev = H.device
+    dxp_dtype = F32
+    if dXp is not None:
+        dxp_dtype = {torch.float32: F32, torch.bfloat16: BF16}[dXp.dtype]
+    if WT is None:
+        WT = torch.empty((max(feplb_grouped_ffn_backward_wt_bytes(g_end - g_begin, d, f), 16),), dtype=torch.uint8, device=dev)
+    if ws is None:
+        ws = torch.empty((feplb_grouped_ffn_workspace_bytes(R_cap, g_end),), dtype=torch.uint8, device=dev)
+    _check(lib().feplb_grouped_ffn_backward(_ptr(Xp), _ptr(offsets), g_begin, g_end, R_cap, d, f,
+                                            _ptr_array(w_gate), _ptr_array(w_up), _ptr_array(w_down),
+                                            _ptr(H), _ptr(AB), _ptr(dYp), _ptr(dXp), dxp_dtype,
+                                            _ptr_array(dw_gate), _ptr_array(dw_up), _ptr_array(dw_down),
+                                            _ptr(WT), WT.numel(), phases, _ptr(ws), ws.numel(), _stream(stream)),
+           "feplb_grouped_ffn_backward")
+    return dXp
 
 
 def feplb_unpermute_combine(Yp, inv, topk_w, T, k, d, Y=None, stream=None):

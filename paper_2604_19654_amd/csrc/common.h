@@ -11,6 +11,13 @@ void set_error(const char* fmt, ...);
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// backward-pass launchers (ffn_backward.hip), used by feplb_grouped_ffn_backward
+hipError_t launch_wgrad(const void* P, int ldp, int M, const void* Q, int ldq, int N, const int* offsets,
+                        int g_begin, int n_groups, int R_cap, void* const* c0, void* const* c1, int n_split,
+                        int ldc, hipStream_t s);
+hipError_t launch_transpose(const void* const* src, int g_begin, int n_groups, int rows, int cols, void* dst,
+                            size_t group_stride, hipStream_t s);
+
 }  // namespace feplb
 
 #define FEPLB_FAIL(code, ...)        \

@@ -32,15 +32,10 @@
 // runs at a time share 8 row panels and 4 weight panels.
 #include <type_traits>
 #include "common.h"
+#include "gemm_device.h"
 
 namespace {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-typedef short i16x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(1))) const void gptr_t;
-typedef __attribute__((address_space(3))) void lptr_t;
+using namespace feplb::dev;
 
 constexpr int BM = 256;      // rows per tile
 constexpr int BNW = 256;     // weight columns per tile
@@ -53,34 +48,6 @@ constexpr int THREADS = 256;
 constexpr int A_STAGE_BYTES = BM * BK * 2;
 constexpr int B_PART_BYTES = BK * 128 * 2;
 constexpr int B_STAGE_BYTES = 2 * B_PART_BYTES;
-constexpr int XCDS = 8;
-
-// 16-byte-per-lane load from global memory straight into LDS (LDS-DMA): lane l's data lands at
-// LDS byte address lds_base + 16*l (lds_base is wave-uniform and travels in M0).  Written as
-// inline assembly so that the loads' completion is tracked by the explicit s_waitcnt vmcnt(n)
-// of the pipeline below: the compiler's own tracking would wait for ALL outstanding loads
-// before any LDS read in a loop, i.e. also for the tiles requested for later steps.
-// The address is a wave-uniform base (scalar register pair) plus a 32-bit per-lane byte offset.
-__device__ __forceinline__ void load_to_lds_16(const char* base, uint32_t lane_off, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
-               :
-               : "v"(lane_off), "s"(base), "s"(lds_base)
-               : "memory", "m0");
-}
-__device__ __forceinline__ const char* wave_uniform(const void* p) {
-  const uint64_t v = (uint64_t)(uintptr_t)p;
-  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
-  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-  return (const char*)(uintptr_t)(((uint64_t)hi << 32) | lo);
-}
-__device__ __forceinline__ uint32_t lds_offset(const void* p) {
-  return (uint32_t)(uintptr_t)p;   // low half of a generic LDS address is the LDS byte offset
-}
-
-struct WeightTable {
-  const void* w0[FEPLB_MAX_GROUPS];  // gate (gate_up) or down (down)
-  const void* w1[FEPLB_MAX_GROUPS];  // up (gate_up only)
-};
 
 // ws layout: int4 header {n_tiles,0,0,0}, then int4 {group, row0, rows, 0} per tile
 constexpr int SCHED_THREADS = 256;
@@ -124,23 +91,17 @@ __global__ __launch_bounds__(SCHED_THREADS) void ffn_schedule_kernel(
   if (i == 0) ws[0] = make_int4(total, 0, 0, 0);
 }
 
-// a * sigmoid(a) with the hardware reciprocal (1 ulp): the result is rounded to bf16 anyway
-__device__ __forceinline__ float silu(float a) { return a * __builtin_amdgcn_rcpf(1.0f + __expf(-a)); }
-
-// two floats -> two bf16 (round to nearest even) in one 32-bit word, first argument in the low half
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-  typedef float f32x2 __attribute__((ext_vector_type(2)));
-  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-  const f32x2 v = {lo, hi};
-  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
-}
-
-// MODE 0: gate_up (+SwiGLU, bf16 out); MODE 1: down (fp32 or bf16 out)
-template <int MODE, bool OUT_BF16>
+// MODE 0: gate_up (+SwiGLU, bf16 out; with SAVE the gate and up products are also stored, as bf16,
+//         in columns [0,N) and [N,2N) of `aux`, for the backward pass);
+// MODE 1: plain GEMM (down, or the input gradient), fp32 or bf16 out;
+// MODE 2: backward of the SwiGLU product: the GEMM result is dH; `aux` holds the saved gate | up
+//         products a | b on entry and their gradients on exit,
+//         da = dH b s (1 + a (1 - s)),  db = dH a s,  s = sigmoid(a); `out` is not used.
+template <int MODE, bool OUT_BF16, bool SAVE>
 __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
     const uint16_t* __restrict__ A, int lda, const int* __restrict__ row_src, int n_src_rows, int src_k,
     const int4* __restrict__ sched, int K, int N, int n_tiles_n, int patch_n, WeightTable wt,
-    void* __restrict__ out, int ldo) {
+    void* __restrict__ out, int ldo, void* aux, int ld_aux) {
   // Separate LDS arrays per stage (not one block with run-time offsets): the compiler can then
   // prove that an LDS-DMA load into one stage and the fragment reads of another stage do not
   // alias, and does not make the reads wait for the loads just issued.
@@ -437,7 +398,7 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
   // No barrier: the region is private to the wave and the LDS executes one wave's
   // instructions in order.
   constexpr int COLS = MODE == 0 ? 64 : 128;                    // output columns of this wave
-  constexpr int ESZ = (MODE == 0 || OUT_BF16) ? 2 : 4;
+  constexpr int ESZ = (MODE == 0 || MODE == 2 || OUT_BF16) ? 2 : 4;
   constexpr int ROW_BYTES = COLS * ESZ;                         // 128, 256 or 512
   constexpr int CH = ROW_BYTES / 16;                            // 16-byte chunks per row
   constexpr int RPI = 64 / CH;                                  // rows per store instruction
@@ -448,56 +409,123 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
   const int csub = (lane / 32) * 4;
   const int col0 = MODE == 0 ? nt * 128 + wn * 64 : nt * 256 + wn * 128;
   const int rd_row = lane / CH, rd_chunk = lane % CH;
-  char* out_wave = (char*)out + ((size_t)(row0 + wm * 128) * ldo + col0) * ESZ;
-#pragma unroll
-  for (int mi = 0; mi < 4; ++mi) {
-    char* wr = ep + l32 * ROW_BYTES;
-    const int sw = swz(l32);
-#pragma unroll
-    for (int nj = 0; nj < (MODE == 0 ? 2 : 4); ++nj)
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const int boff = (nj * 32 + 8 * c + csub) * ESZ;        // byte offset of the piece in its row
-        char* dst = wr + ((((boff >> 4) ^ sw)) << 4) + (boff & 15);
-        float v[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-          v[i] = MODE == 0 ? silu(acc[mi][nj][4 * c + i]) * acc[mi][nj + 2][4 * c + i] : acc[mi][nj][4 * c + i];
-        if (ESZ == 2)
-          *(uint2*)dst = make_uint2(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]));
-        else
-          *(float4*)dst = make_float4(v[0], v[1], v[2], v[3]);
-      }
+  // position of the 8- or 16-byte piece (nj, c) of this lane's row in the staging region
+  auto piece = [&](int nj, int c) -> char* {
+    const int boff = (nj * 32 + 8 * c + csub) * ESZ;            // byte offset of the piece in its row
+    return ep + l32 * ROW_BYTES + ((((boff >> 4) ^ swz(l32))) << 4) + (boff & 15);
+  };
+  // the 32 staged rows leave as whole lines: lanes laid along the rows
+  auto store_lines = [&](int mi, char* dst_wave, int ld_bytes, bool streaming) {
 #pragma unroll
     for (int j = 0; j < 32 / RPI; ++j) {
       const int r = j * RPI + rd_row;                            // row inside this pass
       const uint4 v = *(const uint4*)(ep + r * ROW_BYTES + ((rd_chunk ^ swz(r)) << 4));
-      if (wm * 128 + mi * 32 + r < rows)
-        {
-          typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-          u32x4* dst = (u32x4*)(out_wave + (size_t)(mi * 32 + r) * ldo * ESZ + rd_chunk * 16);
-          const u32x4 vv = {v.x, v.y, v.z, v.w};
-          if (MODE == 1 && !OUT_BF16) __builtin_nontemporal_store(vv, dst); else *dst = vv;
+      if (wm * 128 + mi * 32 + r < rows) {
+        u32x4* dst = (u32x4*)(dst_wave + (size_t)(mi * 32 + r) * ld_bytes + rd_chunk * 16);
+        const u32x4 vv = {v.x, v.y, v.z, v.w};
+        if (streaming) __builtin_nontemporal_store(vv, dst); else *dst = vv;
+      }
+    }
+  };
+  if constexpr (MODE == 2) {
+    // a | b come in as whole lines, pass through the staging region (a in its first 8 KB, b in
+    // the second) to reach the lanes that hold the matching dH values, and leave the same way
+    char* aux_wave = (char*)aux + ((size_t)(row0 + wm * 128) * ld_aux + col0) * 2;
+    const size_t b_shift = (size_t)N * 2;                        // b sits N columns to the right of a
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+      u32x4 la[32 / RPI], lb[32 / RPI];
+#pragma unroll
+      for (int j = 0; j < 32 / RPI; ++j) {
+        const int r = j * RPI + rd_row;
+        la[j] = lb[j] = u32x4{0u, 0u, 0u, 0u};
+        if (wm * 128 + mi * 32 + r < rows) {
+          const char* src = aux_wave + (size_t)(mi * 32 + r) * ld_aux * 2 + rd_chunk * 16;
+          la[j] = *(const u32x4*)src;
+          lb[j] = *(const u32x4*)(src + b_shift);
         }
+      }
+#pragma unroll
+      for (int j = 0; j < 32 / RPI; ++j) {
+        const int r = j * RPI + rd_row;
+        char* q = ep + r * ROW_BYTES + ((rd_chunk ^ swz(r)) << 4);
+        *(u32x4*)q = la[j];
+        *(u32x4*)(q + 8192) = lb[j];
+      }
+#pragma unroll
+      for (int nj = 0; nj < 4; ++nj)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          char* q = piece(nj, c);
+          const uint2 av = *(const uint2*)q, bv = *(const uint2*)(q + 8192);
+          const float a[4] = {bf16_lo(av.x), bf16_hi(av.x), bf16_lo(av.y), bf16_hi(av.y)};
+          const float b[4] = {bf16_lo(bv.x), bf16_hi(bv.x), bf16_lo(bv.y), bf16_hi(bv.y)};
+          float da[4], db[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float dh = acc[mi][nj][4 * c + i];
+            const float sg = __builtin_amdgcn_rcpf(1.0f + __expf(-a[i]));
+            db[i] = dh * a[i] * sg;
+            da[i] = dh * b[i] * sg * (1.0f + a[i] * (1.0f - sg));
+          }
+          *(uint2*)q = make_uint2(pack_bf16(da[0], da[1]), pack_bf16(da[2], da[3]));
+          *(uint2*)(q + 8192) = make_uint2(pack_bf16(db[0], db[1]), pack_bf16(db[2], db[3]));
+        }
+      store_lines(mi, aux_wave, ld_aux * 2, false);
+      ep += 8192;
+      store_lines(mi, aux_wave + b_shift, ld_aux * 2, false);
+      ep -= 8192;
+    }
+  } else {
+    char* out_wave = (char*)out + ((size_t)(row0 + wm * 128) * ldo + col0) * ESZ;
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+#pragma unroll
+      for (int what = 0; what < (MODE == 0 && SAVE ? 3 : 1); ++what) {
+#pragma unroll
+        for (int nj = 0; nj < (MODE == 0 ? 2 : 4); ++nj)
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            char* dst = piece(nj, c);
+            float v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              if (MODE == 0)
+                v[i] = what == 0 ? silu(acc[mi][nj][4 * c + i]) * acc[mi][nj + 2][4 * c + i]
+                                 : acc[mi][what == 1 ? nj : nj + 2][4 * c + i];
+              else
+                v[i] = acc[mi][nj][4 * c + i];
+            }
+            if (ESZ == 2)
+              *(uint2*)dst = make_uint2(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]));
+            else
+              *(float4*)dst = make_float4(v[0], v[1], v[2], v[3]);
+          }
+        if (what == 0)
+          store_lines(mi, out_wave, ldo * ESZ, MODE == 1 && !OUT_BF16);
+        else   // saved gate (what 1) and up (what 2) products
+          store_lines(mi, (char*)aux + ((size_t)(row0 + wm * 128) * ld_aux + (what - 1) * N + col0) * 2,
+                      ld_aux * 2, false);
+      }
     }
   }
 }
 
 int max_tiles_for(int R_cap, int ng) { return R_cap / BM + ng + 1; }
 
-template <int MODE, bool OUT_BF16>
+template <int MODE, bool OUT_BF16, bool SAVE = false>
 hipError_t launch_gemm(const void* A, int lda, const int* row_src, int n_src_rows, int src_k, const int4* sched,
                        int K, int N, int n_tiles_n, int max_tiles, const WeightTable& wt, void* out,
-                       int ldo, hipStream_t s) {
+                       int ldo, hipStream_t s, void* aux = nullptr, int ld_aux = 0) {
   const int patch_n = n_tiles_n % 4 == 0 ? 4 : (n_tiles_n % 2 == 0 ? 2 : 1);
   const int patch_m = 32 / patch_n;
   const int patches_m = (max_tiles + patch_m - 1) / patch_m;
   const int patches = patches_m * (n_tiles_n / patch_n);
   const int patch_rounds = (patches + XCDS - 1) / XCDS;
   const unsigned blocks = (unsigned)patch_rounds * XCDS * 32;
-  hipLaunchKernelGGL((grouped_gemm_kernel<MODE, OUT_BF16>), dim3(blocks), dim3(THREADS), 0,
+  hipLaunchKernelGGL((grouped_gemm_kernel<MODE, OUT_BF16, SAVE>), dim3(blocks), dim3(THREADS), 0,
                      s, (const uint16_t*)A, lda, row_src, n_src_rows, src_k, sched, K, N, n_tiles_n, patch_n, wt,
-                     out, ldo);
+                     out, ldo, aux, ld_aux);
   return hipGetLastError();
 }
 
@@ -508,13 +536,14 @@ extern "C" size_t feplb_grouped_ffn_workspace_bytes(int32_t R_cap, int32_t G) {
   return (size_t)(1 + max_tiles_for(R_cap, G)) * sizeof(int4);
 }
 
-extern "C" int32_t feplb_grouped_ffn(const void* Xp, const int32_t* row_src, int32_t T, int32_t k,
-                                     const int32_t* offsets, int32_t g_begin,
-                                     int32_t g_end, int32_t R_cap, int32_t d, int32_t f,
-                                     const void* const* w_gate, const void* const* w_up,
-                                     const void* const* w_down, void* H, void* Yp,
-                                     int32_t yp_dtype, int32_t phases, void* ws, size_t ws_bytes,
-                                     void* stream) {
+namespace {
+int32_t forward_impl(const void* Xp, const int32_t* row_src, int32_t T, int32_t k,
+                     const int32_t* offsets, int32_t g_begin,
+                     int32_t g_end, int32_t R_cap, int32_t d, int32_t f,
+                     const void* const* w_gate, const void* const* w_up,
+                     const void* const* w_down, void* H, void* AB, void* Yp,
+                     int32_t yp_dtype, int32_t phases, void* ws, size_t ws_bytes,
+                     void* stream) {
   FEPLB_REQUIRE(g_begin >= 0 && g_end >= g_begin && R_cap >= 0 && d >= 0 && f >= 0, FEPLB_EINVAL,
                 "grouped_ffn: negative size or empty range reversed");
   FEPLB_REQUIRE(g_end <= FEPLB_MAX_GROUPS, FEPLB_ESHAPE, "grouped_ffn: g_end=%d above %d", g_end,
@@ -537,8 +566,8 @@ extern "C" int32_t feplb_grouped_ffn(const void* Xp, const int32_t* row_src, int
       FEPLB_REQUIRE(T > 0 && k > 0 && (uint64_t)T * (uint64_t)d * 2 <= 0xffffffffull, FEPLB_ESHAPE,
                     "grouped_ffn: gathering needs T > 0, k > 0 and T*d*2 < 4 GiB (T=%d k=%d d=%d)", T, k, d);
     }
-    FEPLB_REQUIRE(feplb::aligned16(Xp) && feplb::aligned16(H), FEPLB_EALIGN,
-                  "grouped_ffn: Xp/H not 16-byte aligned");
+    FEPLB_REQUIRE(feplb::aligned16(Xp) && feplb::aligned16(H) && feplb::aligned16(AB), FEPLB_EALIGN,
+                  "grouped_ffn: Xp/H/AB not 16-byte aligned");
   }
   if (do_down) {
     FEPLB_REQUIRE(Yp && H && w_down, FEPLB_EINVAL, "grouped_ffn: null Yp/H/w_down");
@@ -574,13 +603,142 @@ extern "C" int32_t feplb_grouped_ffn(const void* Xp, const int32_t* row_src, int
     FEPLB_LAUNCH_CHECK("ffn_schedule_kernel");
   }
   if (do_up) {
-    FEPLB_HIP((launch_gemm<0, true>(Xp, d, row_src, T, k, (const int4*)ws, d, f, f / 128, max_tiles, up_tab, H, f, s)));
+    if (AB)
+      FEPLB_HIP((launch_gemm<0, true, true>(Xp, d, row_src, T, k, (const int4*)ws, d, f, f / 128, max_tiles, up_tab, H, f, s, AB, 2 * f)));
+    else
+      FEPLB_HIP((launch_gemm<0, true>(Xp, d, row_src, T, k, (const int4*)ws, d, f, f / 128, max_tiles, up_tab, H, f, s)));
   }
   if (do_down) {
     if (yp_dtype == FEPLB_BF16)
       FEPLB_HIP((launch_gemm<1, true>(H, f, nullptr, 0, 1, (const int4*)ws, f, d, d / 256, max_tiles, down_tab, Yp, d, s)));
     else
       FEPLB_HIP((launch_gemm<1, false>(H, f, nullptr, 0, 1, (const int4*)ws, f, d, d / 256, max_tiles, down_tab, Yp, d, s)));
+  }
+  return FEPLB_OK;
+}
+}  // namespace
+
+extern "C" int32_t feplb_grouped_ffn(const void* Xp, const int32_t* row_src, int32_t T, int32_t k,
+                                     const int32_t* offsets, int32_t g_begin,
+                                     int32_t g_end, int32_t R_cap, int32_t d, int32_t f,
+                                     const void* const* w_gate, const void* const* w_up,
+                                     const void* const* w_down, void* H, void* Yp,
+                                     int32_t yp_dtype, int32_t phases, void* ws, size_t ws_bytes,
+                                     void* stream) {
+  return forward_impl(Xp, row_src, T, k, offsets, g_begin, g_end, R_cap, d, f, w_gate, w_up, w_down, H,
+                      nullptr, Yp, yp_dtype, phases, ws, ws_bytes, stream);
+}
+
+extern "C" int32_t feplb_grouped_ffn_train(const void* Xp, const int32_t* row_src, int32_t T, int32_t k,
+                                           const int32_t* offsets, int32_t g_begin,
+                                           int32_t g_end, int32_t R_cap, int32_t d, int32_t f,
+                                           const void* const* w_gate, const void* const* w_up,
+                                           const void* const* w_down, void* H, void* AB, void* Yp,
+                                           int32_t yp_dtype, int32_t phases, void* ws, size_t ws_bytes,
+                                           void* stream) {
+  FEPLB_REQUIRE(AB || !(phases & FEPLB_FFN_GATE_UP), FEPLB_EINVAL, "grouped_ffn_train: null AB");
+  return forward_impl(Xp, row_src, T, k, offsets, g_begin, g_end, R_cap, d, f, w_gate, w_up, w_down, H,
+                      AB, Yp, yp_dtype, phases, ws, ws_bytes, stream);
+}
+
+extern "C" size_t feplb_grouped_ffn_backward_wt_bytes(int32_t n_groups, int32_t d, int32_t f) {
+  if (n_groups < 0 || d < 0 || f < 0) return 0;
+  return (size_t)n_groups * 3 * (size_t)d * (size_t)f * 2;
+}
+
+extern "C" int32_t feplb_grouped_ffn_backward(const void* Xp, const int32_t* offsets, int32_t g_begin,
+                                              int32_t g_end, int32_t R_cap, int32_t d, int32_t f,
+                                              const void* const* w_gate, const void* const* w_up,
+                                              const void* const* w_down, const void* H, void* AB,
+                                              const void* dYp, void* dXp, int32_t dxp_dtype,
+                                              void* const* dw_gate, void* const* dw_up,
+                                              void* const* dw_down, void* WT, size_t wt_bytes,
+                                              int32_t phases, void* ws, size_t ws_bytes, void* stream) {
+  FEPLB_REQUIRE(g_begin >= 0 && g_end >= g_begin && R_cap >= 0 && d >= 0 && f >= 0, FEPLB_EINVAL,
+                "grouped_ffn_backward: negative size or empty range reversed");
+  FEPLB_REQUIRE(g_end <= FEPLB_MAX_GROUPS, FEPLB_ESHAPE, "grouped_ffn_backward: g_end=%d above %d", g_end,
+                FEPLB_MAX_GROUPS);
+  FEPLB_REQUIRE((phases & ~FEPLB_BWD_ALL) == 0 && phases != 0, FEPLB_EINVAL,
+                "grouped_ffn_backward: phases=%d", phases);
+  FEPLB_REQUIRE(dxp_dtype == FEPLB_F32 || dxp_dtype == FEPLB_BF16, FEPLB_EINVAL,
+                "grouped_ffn_backward: unknown dxp_dtype %d", dxp_dtype);
+  FEPLB_REQUIRE(d % 256 == 0 && f % 256 == 0 && d > 0 && f > 0, FEPLB_ESHAPE,
+                "grouped_ffn_backward: need d %% 256 == 0 and f %% 256 == 0 (d=%d f=%d)", d, f);
+  const int ng = g_end - g_begin;
+  if (ng == 0) return FEPLB_OK;
+  const bool do_t = phases & FEPLB_BWD_TRANSPOSE, do_d = phases & FEPLB_BWD_DGRAD, do_w = phases & FEPLB_BWD_WGRAD;
+  // the weight-gradient kernel reads whole windows of 32 rows and runs for empty inputs too
+  // (it writes the zero gradients), so the row buffers must hold at least one window
+  FEPLB_REQUIRE(!do_w || R_cap >= 32, FEPLB_ESHAPE, "grouped_ffn_backward: WGRAD needs R_cap >= 32 (R_cap=%d)", R_cap);
+  FEPLB_REQUIRE(offsets, FEPLB_EINVAL, "grouped_ffn_backward: null offsets");
+  // column offsets inside a row travel as 32-bit byte offsets
+  FEPLB_REQUIRE((uint64_t)(2 * (size_t)f + d) * 64 * 2 <= 0xffffffffull, FEPLB_ESHAPE, "grouped_ffn_backward: d, f too large");
+  if (do_t) {
+    FEPLB_REQUIRE(w_gate && w_up && w_down, FEPLB_EINVAL, "grouped_ffn_backward: null weight tables");
+    for (int g = g_begin; g < g_end; ++g) {
+      FEPLB_REQUIRE(w_gate[g] && w_up[g] && w_down[g], FEPLB_EINVAL, "grouped_ffn_backward: null weights of group %d", g);
+      FEPLB_REQUIRE(feplb::aligned16(w_gate[g]) && feplb::aligned16(w_up[g]) && feplb::aligned16(w_down[g]),
+                    FEPLB_EALIGN, "grouped_ffn_backward: weights of group %d not 16-byte aligned", g);
+    }
+  }
+  if (do_t || do_d) {
+    const size_t need_wt = feplb_grouped_ffn_backward_wt_bytes(ng, d, f);
+    FEPLB_REQUIRE(WT && wt_bytes >= need_wt, FEPLB_EWORKSPACE, "grouped_ffn_backward: WT %zu < %zu", wt_bytes, need_wt);
+    FEPLB_REQUIRE(feplb::aligned16(WT), FEPLB_EALIGN, "grouped_ffn_backward: WT not 16-byte aligned");
+  }
+  if (do_d) {
+    FEPLB_REQUIRE(AB && dYp && dXp, FEPLB_EINVAL, "grouped_ffn_backward: null AB/dYp/dXp");
+    FEPLB_REQUIRE(feplb::aligned16(AB) && feplb::aligned16(dYp) && feplb::aligned16(dXp), FEPLB_EALIGN,
+                  "grouped_ffn_backward: AB/dYp/dXp not 16-byte aligned");
+  }
+  if (do_w) {
+    FEPLB_REQUIRE(Xp && H && AB && dYp && dw_gate && dw_up && dw_down, FEPLB_EINVAL,
+                  "grouped_ffn_backward: null Xp/H/AB/dYp or gradient tables");
+    FEPLB_REQUIRE(feplb::aligned16(Xp) && feplb::aligned16(H) && feplb::aligned16(AB) && feplb::aligned16(dYp),
+                  FEPLB_EALIGN, "grouped_ffn_backward: Xp/H/AB/dYp not 16-byte aligned");
+    for (int g = g_begin; g < g_end; ++g) {
+      FEPLB_REQUIRE(dw_gate[g] && dw_up[g] && dw_down[g], FEPLB_EINVAL, "grouped_ffn_backward: null gradient of group %d", g);
+      FEPLB_REQUIRE(feplb::aligned16(dw_gate[g]) && feplb::aligned16(dw_up[g]) && feplb::aligned16(dw_down[g]),
+                    FEPLB_EALIGN, "grouped_ffn_backward: gradient of group %d not 16-byte aligned", g);
+    }
+  }
+  const int max_tiles = max_tiles_for(R_cap, ng);
+  if (do_d || (phases & FEPLB_BWD_SCHEDULE)) {
+    const size_t need = (size_t)(1 + max_tiles) * sizeof(int4);
+    FEPLB_REQUIRE(ws && ws_bytes >= need, FEPLB_EWORKSPACE, "grouped_ffn_backward: workspace %zu < %zu", ws_bytes, need);
+    FEPLB_REQUIRE(feplb::aligned16(ws), FEPLB_EALIGN, "grouped_ffn_backward: workspace not 16-byte aligned");
+  }
+  hipStream_t s = (hipStream_t)stream;
+  const size_t df = (size_t)d * f;
+  if ((phases & FEPLB_BWD_SCHEDULE) && R_cap > 0) {
+    hipLaunchKernelGGL(ffn_schedule_kernel, dim3(1), dim3(SCHED_THREADS), 0, s, offsets, g_begin, g_end, R_cap,
+                       max_tiles, (int4*)ws);
+    FEPLB_LAUNCH_CHECK("ffn_schedule_kernel");
+  }
+  if (do_t) {
+    // per group: Wd^T [d,f], then Wg^T [f,d] and Wu^T [f,d], the last two forming [2f,d]
+    uint16_t* wt0 = (uint16_t*)WT;
+    FEPLB_HIP(feplb::launch_transpose(w_down, g_begin, ng, f, d, wt0, 3 * df, s));
+    FEPLB_HIP(feplb::launch_transpose(w_gate, g_begin, ng, d, f, wt0 + df, 3 * df, s));
+    FEPLB_HIP(feplb::launch_transpose(w_up, g_begin, ng, d, f, wt0 + 2 * df, 3 * df, s));
+  }
+  WeightTable dT{}, guT{};
+  for (int g = g_begin; g < g_end; ++g) {
+    const uint16_t* base = (const uint16_t*)WT + (size_t)(g - g_begin) * 3 * df;
+    dT.w0[g] = base;
+    guT.w0[g] = base + df;
+  }
+  if (do_w && R_cap > 0)   // dW_down = H^T dYp: before DGRAD, which does not touch H or dYp
+    FEPLB_HIP(feplb::launch_wgrad(H, f, f, dYp, d, d, offsets, g_begin, ng, R_cap, dw_down, nullptr, d, d, s));
+  if (do_d && R_cap > 0)   // dH = dYp Wd^T, turned into [da | db] in place over the saved [a | b]
+    FEPLB_HIP((launch_gemm<2, true>(dYp, d, nullptr, 0, 1, (const int4*)ws, d, f, f / 256, max_tiles, dT, nullptr, 0, s, AB, 2 * f)));
+  if (do_w && R_cap > 0)   // [dW_gate | dW_up] = Xp^T [da | db]
+    FEPLB_HIP(feplb::launch_wgrad(Xp, d, d, AB, 2 * f, 2 * f, offsets, g_begin, ng, R_cap, dw_gate, dw_up, f, f, s));
+  if (do_d && R_cap > 0) {   // dXp = [da | db] [Wg^T; Wu^T]
+    if (dxp_dtype == FEPLB_BF16)
+      FEPLB_HIP((launch_gemm<1, true>(AB, 2 * f, nullptr, 0, 1, (const int4*)ws, 2 * f, d, d / 256, max_tiles, guT, dXp, d, s)));
+    else
+      FEPLB_HIP((launch_gemm<1, false>(AB, 2 * f, nullptr, 0, 1, (const int4*)ws, 2 * f, d, d / 256, max_tiles, guT, dXp, d, s)));
   }
   return FEPLB_OK;
 }

@@ -1,0 +1,215 @@
+"""Parity of the HIP backward pass of the grouped expert FFN with the CPU oracle, through the
+C ABI.  The oracle differentiates the float64 definition; the library keeps its activations and
+their gradients in bf16, so every output row is held to BWD_RMS_TOL (root-mean-square error) and
+BWD_MAX_TOL (largest error) of that row's RMS; tests/util.py derives both bars.  Beside each result the tests print what a float64
+computation that merely stores a, b, H, da, db in bf16 would get: a diagnostic, not a bound.
+Needs an MI355X: run with -m gpu."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2604_19654_amd as fe
+from paper_2604_19654_amd import binding as B
+from oracle import feplb_oracle as orc
+from tests.util import f64, row_rel_err, row_rms_err, bf16_rounding_excess, BWD_RMS_TOL, BWD_MAX_TOL
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def make_weights(G, d, f, seed):
+    g = torch.Generator().manual_seed(seed)
+    return [tuple((torch.randn(s, generator=g) * 0.05).to(torch.bfloat16) for s in ((d, f), (d, f), (f, d)))
+            for _ in range(G)]
+
+
+def run_forward_backward(sizes, d, f, dxp_dtype, pad=37, seed=7, poison=float("nan")):
+    """One training step of the library on groups of the given sizes; rows past R hold `poison`."""
+    G = len(sizes)
+    offsets = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    R = int(offsets[-1])
+    R_cap = max(R + pad, 32)
+    gen = torch.Generator().manual_seed(seed)
+    Xp = torch.randn((R_cap, d), generator=gen).to(torch.bfloat16)
+    dYp = torch.randn((R_cap, d), generator=gen).to(torch.bfloat16)
+    Xp[R:] = poison
+    dYp[R:] = poison
+    W = make_weights(G, d, f, seed + 4)
+    Wd = [tuple(m.to(DEV) for m in w) for w in W]
+    H = torch.full((R_cap, f), poison, dtype=torch.bfloat16, device=DEV)
+    AB = torch.full((R_cap, 2 * f), poison, dtype=torch.bfloat16, device=DEV)
+    Yp = torch.full((R_cap, d), 512.0, dtype=torch.float32, device=DEV)
+    dXp = torch.full((R_cap, d), 512.0, dtype=dxp_dtype, device=DEV)
+    off_dev = torch.from_numpy(offsets).to(DEV)
+    Xp_dev, dYp_dev = Xp.to(DEV), dYp.to(DEV)
+    wg, wu, wd = ([w[i] for w in Wd] for i in range(3))
+    fe.feplb_grouped_ffn(Xp_dev, off_dev, 0, G, d, f, wg, wu, wd, H, Yp, AB=AB)
+    torch.cuda.synchronize()
+    AB_saved = AB.clone()
+    dW = [tuple(torch.full(s, 7.0, dtype=torch.float32, device=DEV) for s in ((d, f), (d, f), (f, d))) for _ in range(G)]
+    B.feplb_grouped_ffn_backward(Xp_dev, off_dev, 0, G, d, f, wg, wu, wd, H, AB, dYp_dev, dXp,
+                                 [w[0] for w in dW], [w[1] for w in dW], [w[2] for w in dW])
+    torch.cuda.synchronize()
+    return dict(offsets=offsets, R=R, R_cap=R_cap, Xp=Xp, dYp=dYp, W=W, H=H, AB_saved=AB_saved, dAB=AB, Yp=Yp,
+                dXp=dXp, dW=dW)
+
+
+def oracle_backward(r):
+    R = r["R"]
+    Wo = [tuple(f64(m) for m in w) for w in r["W"]]
+    return orc.grouped_ffn_backward(f64(r["Xp"])[:R], r["offsets"], Wo, f64(r["dYp"])[:R]), Wo
+
+
+def bf16_round(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).to(torch.bfloat16).to(torch.float64).numpy()
+
+
+def storage_format_floor(r, dXp_o, grads_o, Wo):
+    """Worst row error of a float64 backward whose only inexactness is keeping a, b, H, da, db in
+    bf16 (diagnostic printed beside the library's figures)."""
+    R = r["R"]
+    X, dY = f64(r["Xp"])[:R], f64(r["dYp"])[:R]
+    worst = np.zeros(4)     # dXp rms, dXp max, weights rms, weights max
+    for g, (wg, wu, wd) in enumerate(Wo):
+        lo, hi = int(r["offsets"][g]), int(r["offsets"][g + 1])
+        if hi == lo:
+            continue
+        x, dy = X[lo:hi], dY[lo:hi]
+        a0, b0 = x @ wg, x @ wu
+        h = bf16_round(a0 / (1.0 + np.exp(-a0)) * b0)
+        a, b = bf16_round(a0), bf16_round(b0)
+        sg = 1.0 / (1.0 + np.exp(-a))
+        dh = dy @ wd.T
+        da, db = bf16_round(dh * b * sg * (1.0 + a * (1.0 - sg))), bf16_round(dh * a * sg)
+        dx = da @ wg.T + db @ wu.T
+        worst[0] = max(worst[0], row_rms_err(dx, dXp_o[lo:hi]).max())
+        worst[1] = max(worst[1], row_rel_err(dx, dXp_o[lo:hi]).max())
+        for got, want in zip((x.T @ da, x.T @ db, h.T @ dy), grads_o[g]):
+            worst[2] = max(worst[2], row_rms_err(got, want).max())
+            worst[3] = max(worst[3], row_rel_err(got, want).max())
+    return "bf16 storage alone: dXp rms %.5f max %.5f, weights rms %.5f max %.5f" % tuple(worst)
+
+
+def check_rows(got, want, what):
+    """Both bars on every row; returns (worst rms error, worst largest error)."""
+    e_rms, e_max = row_rms_err(got, want), row_rel_err(got, want)
+    assert e_rms.max() <= BWD_RMS_TOL, f"{what}: rms error {e_rms.max():.5f} of the row RMS"
+    assert e_max.max() <= BWD_MAX_TOL, f"{what}: largest error {e_max.max():.5f} of the row RMS"
+    return float(e_rms.max()), float(e_max.max())
+
+
+def check_weight_grads(r, grads_o, label):
+    worst = (0.0, 0.0)
+    for g, (got3, want3) in enumerate(zip(r["dW"], grads_o)):
+        rows = int(r["offsets"][g + 1] - r["offsets"][g])
+        for got, want, name in zip(got3, want3, ("dW_gate", "dW_up", "dW_down")):
+            gv = f64(got)
+            if rows == 0:
+                assert not gv.any(), f"{label}: {name}[{g}] of an empty group is not zero"
+                continue
+            e = check_rows(gv, want, f"{label}: {name}[{g}] ({rows} rows)")
+            worst = (max(worst[0], e[0]), max(worst[1], e[1]))
+    return worst
+
+
+@pytest.mark.parametrize("sizes,d,f", [([128, 0, 1, 129, 300, 0, 64, 255], 256, 256),
+                                       ([5, 700], 512, 256), ([0, 0, 0], 256, 256), ([1], 768, 256),
+                                       ([3], 256, 256), ([33, 31, 32, 64, 65], 256, 512),
+                                       ([0, 40, 0], 256, 256)])
+@pytest.mark.parametrize("dxp_dtype", [torch.float32, torch.bfloat16])
+def test_grouped_ffn_backward_parity(sizes, d, f, dxp_dtype):
+    say(f"ffn backward sizes={sizes} d={d} f={f} {dxp_dtype}")
+    r = run_forward_backward(sizes, d, f, dxp_dtype)
+    R = r["R"]
+    (dXp_o, grads_o), Wo = oracle_backward(r)
+    if R:
+        # what the forward kept: a | b within a bf16 rounding step of the float64 products
+        X64 = f64(r["Xp"])[:R]
+        a_o = np.zeros((R, f)); b_o = np.zeros((R, f))
+        for g in range(len(sizes)):
+            lo, hi = int(r["offsets"][g]), int(r["offsets"][g + 1])
+            a_o[lo:hi] = X64[lo:hi] @ Wo[g][0]
+            b_o[lo:hi] = X64[lo:hi] @ Wo[g][1]
+        ea = bf16_rounding_excess(f64(r["AB_saved"])[:R, :f], a_o)
+        eb = bf16_rounding_excess(f64(r["AB_saved"])[:R, f:], b_o)
+        ex = check_rows(f64(r["dXp"])[:R], dXp_o, "dXp")
+        say(f"  saved a, b rounding excess {ea:.3f} {eb:.3f} (<= 1)  dXp rms {ex[0]:.5f} max {ex[1]:.5f}")
+        assert ea <= 1.0 and eb <= 1.0
+    worst = check_weight_grads(r, grads_o, "parity")
+    say(f"  weight gradients rms {worst[0]:.5f} max {worst[1]:.5f} (<= {BWD_RMS_TOL}, {BWD_MAX_TOL})")
+    say("  " + storage_format_floor(r, dXp_o, grads_o, Wo))
+    # rows past R are never written
+    assert (r["dXp"][R:].float() == 512.0).all()
+    assert torch.isnan(r["dAB"][R:].float()).all() and torch.isnan(r["H"][R:].float()).all()
+
+
+def test_grouped_ffn_backward_larger_ragged_case_and_repeatability():
+    # several row tiles per group, contraction tails of every residue class, f != d
+    sizes = [517, 2, 1031, 0, 255, 770, 96, 1]
+    d, f = 1024, 768
+    say(f"ffn backward sizes={sizes} d={d} f={f}")
+    r = run_forward_backward(sizes, d, f, torch.float32, poison=512.0)
+    (dXp_o, grads_o), Wo = oracle_backward(r)
+    ex = check_rows(f64(r["dXp"])[:r["R"]], dXp_o, "dXp")
+    worst = check_weight_grads(r, grads_o, "larger")
+    say(f"  dXp rms {ex[0]:.5f} max {ex[1]:.5f}  weight gradients rms {worst[0]:.5f} max {worst[1]:.5f}")
+    say("  " + storage_format_floor(r, dXp_o, grads_o, Wo))
+    r2 = run_forward_backward(sizes, d, f, torch.float32, poison=512.0)
+    assert torch.equal(r["dXp"], r2["dXp"]) and torch.equal(r["dAB"], r2["dAB"])
+    for a3, b3 in zip(r["dW"], r2["dW"]):
+        assert all(torch.equal(a, b) for a, b in zip(a3, b3))
+
+
+def test_grouped_ffn_backward_refuses_bad_arguments():
+    d = f = 256
+    z = torch.zeros((64, d), dtype=torch.bfloat16, device=DEV)
+    ab = torch.zeros((64, 2 * f), dtype=torch.bfloat16, device=DEV)
+    off = torch.tensor([0, 64], dtype=torch.int32, device=DEV)
+    w = [torch.zeros((d, f), dtype=torch.bfloat16, device=DEV)]
+    dw = [torch.zeros((d, f), dtype=torch.float32, device=DEV)]
+    dx = torch.zeros((64, d), dtype=torch.float32, device=DEV)
+    with pytest.raises(B.FeplbError):      # f not a multiple of 256
+        B.feplb_grouped_ffn_backward(z, off, 0, 1, d, 128, w, w, w, z, ab, z, dx, dw, dw, dw)
+    with pytest.raises(B.FeplbError):      # scratch for the transposed weights too small
+        B.feplb_grouped_ffn_backward(z, off, 0, 1, d, f, w, w, w, z, ab, z, dx, dw, dw, dw,
+                                     WT=torch.zeros((1024,), dtype=torch.uint8, device=DEV))
+    small = torch.zeros((16, d), dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(B.FeplbError):      # fewer than 32 rows of capacity for the weight gradients
+        B.feplb_grouped_ffn_backward(small, off, 0, 1, d, f, w, w, w, small, ab[:16], small, dx[:16], dw, dw, dw)
+    torch.cuda.synchronize()
+
+
+def test_weight_gradients_add_up_over_a_split_of_the_rows():
+    # one group of n rows against the same rows as two groups with the same matrices: da | db
+    # are computed row by row, so the gradients must agree up to the order of the fp32 sums --
+    # far below the float bar, and sensitive to every row at a window or group boundary
+    d, f = 256, 256
+    for n, cut in [(100, 37), (64, 32), (45, 1), (300, 257), (31, 30)]:
+        say(f"ffn backward split n={n} cut={cut}")
+        gen = torch.Generator().manual_seed(n)
+        Xp = torch.randn((n + 50, d), generator=gen).to(torch.bfloat16).to(DEV)
+        dYp = torch.randn((n + 50, d), generator=gen).to(torch.bfloat16).to(DEV)
+        w = make_weights(1, d, f, 3)[0]
+        w = tuple(m.to(DEV) for m in w)
+        res = []
+        for sizes in ([n], [cut, n - cut]):
+            G = len(sizes)
+            off = torch.tensor(np.concatenate([[0], np.cumsum(sizes)]), dtype=torch.int32, device=DEV)
+            H = torch.zeros((n + 50, f), dtype=torch.bfloat16, device=DEV)
+            AB = torch.zeros((n + 50, 2 * f), dtype=torch.bfloat16, device=DEV)
+            Yp = torch.zeros((n + 50, d), dtype=torch.float32, device=DEV)
+            dXp = torch.zeros((n + 50, d), dtype=torch.float32, device=DEV)
+            wl = [[w[i]] * G for i in range(3)]
+            dW = [[torch.zeros(s, dtype=torch.float32, device=DEV) for _ in range(G)] for s in ((d, f), (d, f), (f, d))]
+            fe.feplb_grouped_ffn(Xp, off, 0, G, d, f, *wl, H, Yp, AB=AB)
+            B.feplb_grouped_ffn_backward(Xp, off, 0, G, d, f, *wl, H, AB, dYp, dXp, *dW)
+            torch.cuda.synchronize()
+            res.append((dXp, [sum(m.double() for m in mats) for mats in dW]))
+        assert torch.equal(res[0][0], res[1][0])
+        for one, two in zip(res[0][1], res[1][1]):
+            scale = one.pow(2).mean().sqrt().item()
+            assert (one - two).abs().max().item() <= 1e-5 * scale

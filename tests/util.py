@@ -19,6 +19,35 @@ def i64(t: torch.Tensor) -> np.ndarray:
 ROW_TOL = 2e-2
 
 
+# Float bars for the backward pass, which the benchmark spec does not state.  The library stores
+# the gate and up products a, b, the activations H and the gradients da, db in bf16 (they are
+# MFMA operands), and the float64 oracle stores nothing rounded.  One bf16 rounding perturbs a
+# value by a relative 2^-9 at most, about 1e-3 in the root mean square; every gradient term
+# carries about three of them (the stored factor itself and, for da and db, the stored a and
+# b it was computed from, with sensitivities between 1 and 1.3), so the error of an output row,
+# taken in the root mean square over the row, is sqrt(3) * 1.2 * 1e-3 ~ 2.5e-3 of the row's RMS
+# whatever the number of rows summed (error and value grow alike).  A float64 computation that
+# only rounds those five tensors measures 0.003 .. 0.0045 on every shape tried, from one-row
+# groups to thousands of rows.  BWD_RMS_TOL is 1e-2.
+# The largest single error of a row is heavy-tailed instead: da is a product of three random
+# factors, and a one-row group has no sum to average over, so that same computation reaches
+# 0.01 .. 0.06 of the row RMS.  BWD_MAX_TOL = 8e-2 (four times the forward bar) only guards
+# against isolated wrong elements; the RMS bar is the one that carries the parity claim.
+BWD_RMS_TOL = 1e-2
+BWD_MAX_TOL = 8e-2
+
+
+def row_rms_err(got: np.ndarray, want: np.ndarray) -> np.ndarray:
+    """rms_i(got - want) / rms_i(want) per row; all-zero oracle rows must match exactly."""
+    err = np.sqrt(((got - want) ** 2).mean(axis=1))
+    rms = np.sqrt((want ** 2).mean(axis=1))
+    out = np.zeros_like(err)
+    nz = rms > 0
+    out[nz] = err[nz] / rms[nz]
+    out[~nz] = np.where(err[~nz] == 0, 0.0, np.inf)
+    return out
+
+
 def row_rel_err(got: np.ndarray, want: np.ndarray) -> np.ndarray:
     """max_i |got - want| / rms_i(want) per row; rows whose oracle value is all
     zero must match exactly (reported as 0 or inf)."""
