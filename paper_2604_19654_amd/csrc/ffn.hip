@@ -529,11 +529,14 @@ hipError_t launch_gemm(const void* A, int lda, const int* row_src, int n_src_row
   return hipGetLastError();
 }
 
+// workspace: the tile table, then (backward pass only) the groups ordered by row count
+size_t table_bytes(int R_cap, int ng) { return (size_t)(1 + max_tiles_for(R_cap, ng)) * sizeof(int4); }
+
 }  // namespace
 
 extern "C" size_t feplb_grouped_ffn_workspace_bytes(int32_t R_cap, int32_t G) {
   if (R_cap < 0 || G < 0) return 0;
-  return (size_t)(1 + max_tiles_for(R_cap, G)) * sizeof(int4);
+  return table_bytes(R_cap, G) + FEPLB_MAX_GROUPS * sizeof(int);
 }
 
 namespace {
@@ -703,8 +706,9 @@ extern "C" int32_t feplb_grouped_ffn_backward(const void* Xp, const int32_t* off
     }
   }
   const int max_tiles = max_tiles_for(R_cap, ng);
-  if (do_d || (phases & FEPLB_BWD_SCHEDULE)) {
-    const size_t need = (size_t)(1 + max_tiles) * sizeof(int4);
+  const size_t order_at = table_bytes(R_cap, ng);
+  {
+    const size_t need = order_at + FEPLB_MAX_GROUPS * sizeof(int);
     FEPLB_REQUIRE(ws && ws_bytes >= need, FEPLB_EWORKSPACE, "grouped_ffn_backward: workspace %zu < %zu", ws_bytes, need);
     FEPLB_REQUIRE(feplb::aligned16(ws), FEPLB_EALIGN, "grouped_ffn_backward: workspace not 16-byte aligned");
   }
@@ -715,6 +719,10 @@ extern "C" int32_t feplb_grouped_ffn_backward(const void* Xp, const int32_t* off
                        max_tiles, (int4*)ws);
     FEPLB_LAUNCH_CHECK("ffn_schedule_kernel");
   }
+  // the order in which the weight-gradient grid walks the groups is rebuilt by every WGRAD call
+  if (do_w && R_cap > 0)
+    FEPLB_HIP(feplb::launch_wgrad_order(offsets, g_begin, ng, R_cap, (int*)((char*)ws + order_at), s));
+  const int* order = (const int*)((const char*)ws + order_at);
   if (do_t) {
     // per group: Wd^T [d,f], then Wg^T [f,d] and Wu^T [f,d], the last two forming [2f,d]
     uint16_t* wt0 = (uint16_t*)WT;
@@ -729,11 +737,11 @@ extern "C" int32_t feplb_grouped_ffn_backward(const void* Xp, const int32_t* off
     guT.w0[g] = base + df;
   }
   if (do_w && R_cap > 0)   // dW_down = H^T dYp: before DGRAD, which does not touch H or dYp
-    FEPLB_HIP(feplb::launch_wgrad(H, f, f, dYp, d, d, offsets, g_begin, ng, R_cap, dw_down, nullptr, d, d, s));
+    FEPLB_HIP(feplb::launch_wgrad(H, f, f, dYp, d, d, offsets, order, g_begin, ng, R_cap, dw_down, nullptr, d, d, s));
   if (do_d && R_cap > 0)   // dH = dYp Wd^T, turned into [da | db] in place over the saved [a | b]
     FEPLB_HIP((launch_gemm<2, true>(dYp, d, nullptr, 0, 1, (const int4*)ws, d, f, f / 256, max_tiles, dT, nullptr, 0, s, AB, 2 * f)));
   if (do_w && R_cap > 0)   // [dW_gate | dW_up] = Xp^T [da | db]
-    FEPLB_HIP(feplb::launch_wgrad(Xp, d, d, AB, 2 * f, 2 * f, offsets, g_begin, ng, R_cap, dw_gate, dw_up, f, f, s));
+    FEPLB_HIP(feplb::launch_wgrad(Xp, d, d, AB, 2 * f, 2 * f, offsets, order, g_begin, ng, R_cap, dw_gate, dw_up, f, f, s));
   if (do_d && R_cap > 0) {   // dXp = [da | db] [Wg^T; Wu^T]
     if (dxp_dtype == FEPLB_BF16)
       FEPLB_HIP((launch_gemm<1, true>(AB, 2 * f, nullptr, 0, 1, (const int4*)ws, 2 * f, d, d / 256, max_tiles, guT, dXp, d, s)));

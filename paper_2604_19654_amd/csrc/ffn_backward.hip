@@ -34,9 +34,29 @@ struct OutTable {
   void* c1[FEPLB_MAX_GROUPS];   // output matrix for columns [n_split, 2 n_split), or unused
 };
 
+// order[i] = the group (relative to g_begin) with the i-th most rows, ties by group index.  The
+// weight-gradient grid walks the groups in this order: a tile's run time is proportional to its
+// group's row count, and workgroups start in grid order, so the long tiles go first and the last
+// compute units to finish are busy with short ones (empty groups, which only write zeros, last).
+__global__ __launch_bounds__(FEPLB_MAX_GROUPS) void wgrad_order_kernel(const int* __restrict__ offsets, int g_begin,
+                                                                       int n_groups, int R_cap, int* __restrict__ order) {
+  __shared__ int rows[FEPLB_MAX_GROUPS];
+  const int i = threadIdx.x;
+  if (i < n_groups) {
+    const int lo = min(offsets[g_begin + i], R_cap);
+    rows[i] = max(min(offsets[g_begin + i + 1], R_cap), lo) - lo;
+  }
+  __syncthreads();
+  if (i < n_groups) {
+    int rank = 0;
+    for (int j = 0; j < n_groups; ++j) rank += rows[j] > rows[i] || (rows[j] == rows[i] && j < i);
+    order[rank] = i;
+  }
+}
+
 __global__ __launch_bounds__(THREADS) void wgrad_gemm_kernel(
     const uint16_t* __restrict__ P, int ldp, const uint16_t* __restrict__ Q, int ldq,
-    const int* __restrict__ offsets, int g_begin, int n_groups, int R_cap,
+    const int* __restrict__ offsets, const int* __restrict__ order, int g_begin, int n_groups, int R_cap,
     int m_tiles, int n_tiles, int patch_n, int n_split, OutTable out, int ldc) {
   __shared__ __attribute__((aligned(1024))) char lds_p0[STAGE_BYTES];
   __shared__ __attribute__((aligned(1024))) char lds_p1[STAGE_BYTES];
@@ -65,14 +85,14 @@ __global__ __launch_bounds__(THREADS) void wgrad_gemm_kernel(
   const int patches_n = n_tiles / patch_n;
   const int per_group = patches_m * patches_n;
   const int patch_all = (slot / 32) * XCDS + xcd;
-  const int gi = patch_all / per_group;
-  if (gi >= n_groups) return;
+  const int slot_g = patch_all / per_group;
+  if (slot_g >= n_groups) return;
   const int patch = patch_all % per_group;
   const int within = slot % 32;
   const int mt = (patch / patches_n) * patch_m + within % patch_m;
   const int nt = (patch % patches_n) * patch_n + within / patch_m;
   if (mt >= m_tiles) return;
-  const int g = g_begin + gi;
+  const int g = g_begin + order[slot_g];
   const int lo = __builtin_amdgcn_readfirstlane(min(offsets[g], R_cap));
   const int hi = __builtin_amdgcn_readfirstlane(max(min(offsets[g + 1], R_cap), lo));
   const int KT = (hi - lo + BK - 1) / BK;
@@ -141,17 +161,30 @@ __global__ __launch_bounds__(THREADS) void wgrad_gemm_kernel(
   // fragment registers, double-buffered over the two 16-row slices of a step:
   // [buf][j] j < 4: P block j, else Q block j - 4; lo = rows 0..3 of the lane's eight, hi = 4..7
   u32x2 fl[2][8], fh[2][8];
-  // read r of 16: fragment r / 2, half r % 2, masked with m (two registers)
-  auto read_frag = [&](auto st, int ks, int buf, int r, const uint32_t* m) {
+  // read r of 16: fragment r / 2, half r % 2
+  auto read_frag = [&](auto st, int ks, int buf, int r) {
     typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
     const int j = r / 2;
     const char* base = j < 4 ? stage_p(st) + wm * PART_BYTES : stage_q(st) + wn * PART_BYTES;
     const char* p = base + ks * 16 * 256 + frag_off[j % 4] + (r % 2) * 4 * 256;
     const u32x2 v = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)p));
     if (r % 2 == 0)
-      fl[buf][j] = u32x2{v.x & m[0], v.y & m[1]};
+      fl[buf][j] = v;
     else
-      fh[buf][j] = u32x2{v.x & m[2], v.y & m[3]};
+      fh[buf][j] = v;
+  };
+  // Row mask of the fragments in `buf` (slice ks = buf), all ones unless they belong to the
+  // group's last window.  Applied in the half step that read them, behind its last reads and
+  // between its later MFMAs, so that neither the LDS latency nor the 32 ANDs are exposed.
+  auto mask_frags = [&](int buf, bool last) {
+    uint32_t m[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) m[v] = last ? tail[buf][v] : 0xffffffffu;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      fl[buf][j] = u32x2{fl[buf][j].x & m[0], fl[buf][j].y & m[1]};
+      fh[buf][j] = u32x2{fh[buf][j].x & m[2], fh[buf][j].y & m[3]};
+    }
   };
   auto mfma16 = [&](int buf) {
 #pragma unroll
@@ -166,10 +199,6 @@ __global__ __launch_bounds__(THREADS) void wgrad_gemm_kernel(
         acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, pf, acc[mi][nj], 0, 0, 0);
       }
   };
-  auto pick_mask = [&](bool last, int ks, uint32_t* m) {
-#pragma unroll
-    for (int v = 0; v < 4; ++v) m[v] = last ? tail[ks][v] : 0xffffffffu;
-  };
 
   // Software pipeline.  Step kt computes tile kt from stage kt % 5, in two halves of 16 MFMAs;
   // its barrier sits between the halves, when every wave holds the last fragments of tile kt.
@@ -183,20 +212,21 @@ __global__ __launch_bounds__(THREADS) void wgrad_gemm_kernel(
     constexpr std::integral_constant<int, (s + 1) % NS> nxt{};
     constexpr std::integral_constant<int, (s + 4) % NS> req{};
     const int row_req = window(min(kt + 4, KT - 1));
-    uint32_t m_cur[4], m_nxt[4];
-    pick_mask(kt == KT - 1, 1, m_cur);
-    pick_mask(kt + 1 == KT - 1, 0, m_nxt);
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       issue_q(req, row_req, q);
 #pragma unroll
-      for (int r = 4 * q; r < 4 * q + 4; ++r) read_frag(cur, 1, 1, r, m_cur);
+      for (int r = 4 * q; r < 4 * q + 4; ++r) read_frag(cur, 1, 1, r);
     }
+    mask_frags(1, kt == KT - 1);
     mfma16(0);
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);               // 1 MFMA
+      if (i < 8)
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);             // 2 LDS reads
+      else
+        __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);             // 5 VALU (the masking)
     }
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_waitcnt(0x4074);   // vmcnt(20) lgkmcnt(0)
@@ -205,13 +235,17 @@ __global__ __launch_bounds__(THREADS) void wgrad_gemm_kernel(
     for (int q = 0; q < 4; ++q) {
       issue_p(req, row_req, q);
 #pragma unroll
-      for (int r = 4 * q; r < 4 * q + 4; ++r) read_frag(nxt, 0, 0, r, m_nxt);
+      for (int r = 4 * q; r < 4 * q + 4; ++r) read_frag(nxt, 0, 0, r);
     }
+    mask_frags(0, kt + 1 == KT - 1);
     mfma16(1);
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      if (i < 8)
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      else
+        __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
   };
@@ -240,12 +274,9 @@ __global__ __launch_bounds__(THREADS) void wgrad_gemm_kernel(
     for (int q = 0; q < 4; ++q) issue_p(c3, window(min(3, KT - 1)), q);
     __builtin_amdgcn_s_waitcnt(0x4f78);   // vmcnt(24): tile 0 has landed
     __syncthreads();
-    {
-      uint32_t m0[4];
-      pick_mask(KT == 1, 0, m0);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) read_frag(c0, 0, 0, r, m0);
-    }
+    for (int r = 0; r < 16; ++r) read_frag(c0, 0, 0, r);
+    mask_frags(0, KT == 1);
     int kt = 0;
     for (; kt + 5 <= KT; kt += 5) {
       step(c0, kt);
@@ -349,8 +380,8 @@ namespace feplb {
 // Q [R_cap, ldq] columns [0, N); output fp32 row-major with row stride ldc; columns of the
 // product at or past n_split go to c1[g] (shifted by n_split).  M, N, n_split multiples of 256.
 hipError_t launch_wgrad(const void* P, int ldp, int M, const void* Q, int ldq, int N, const int* offsets,
-                        int g_begin, int n_groups, int R_cap, void* const* c0, void* const* c1, int n_split,
-                        int ldc, hipStream_t s) {
+                        const int* order, int g_begin, int n_groups, int R_cap, void* const* c0, void* const* c1,
+                        int n_split, int ldc, hipStream_t s) {
   OutTable tab{};
   for (int i = 0; i < n_groups; ++i) {
     tab.c0[g_begin + i] = c0[g_begin + i];
@@ -363,8 +394,14 @@ hipError_t launch_wgrad(const void* P, int ldp, int M, const void* Q, int ldq, i
   const long patches = (long)per_group * n_groups;
   const unsigned blocks = (unsigned)((patches + XCDS - 1) / XCDS) * XCDS * 32;
   hipLaunchKernelGGL(wgrad_gemm_kernel, dim3(blocks), dim3(THREADS), 0, s, (const uint16_t*)P, ldp,
-                     (const uint16_t*)Q, ldq, offsets, g_begin, n_groups, R_cap, m_tiles, n_tiles, patch_n,
+                     (const uint16_t*)Q, ldq, offsets, order, g_begin, n_groups, R_cap, m_tiles, n_tiles, patch_n,
                      n_split, tab, ldc);
+  return hipGetLastError();
+}
+
+// order[0 .. n_groups) = the groups of [g_begin, g_begin + n_groups) by descending row count
+hipError_t launch_wgrad_order(const int* offsets, int g_begin, int n_groups, int R_cap, int* order, hipStream_t s) {
+  hipLaunchKernelGGL(wgrad_order_kernel, dim3(1), dim3(FEPLB_MAX_GROUPS), 0, s, offsets, g_begin, n_groups, R_cap, order);
   return hipGetLastError();
 }
 
