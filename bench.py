@@ -134,6 +134,38 @@ def _permute_ms(p, steps):
     return e0.elapsed_ms(e1) / steps
 
 
+def training_leg(p, steps):
+    """Forward (keeping the gate/up products) and backward of the grouped FFN on the step's own
+    groups and token rows, with a synthetic upstream gradient; reported beside the forward step,
+    not part of `value`."""
+    import torch
+    from paper_2604_19654_amd import binding as B, runner
+    from paper_2604_19654_amd.training import FfnTrainingStep, time_phases
+    lay, b, wl = p.layer, p.layer.buf, p.wl
+    G = len(p.groups)
+    dev = wl.X.device
+    W = runner.group_weights(p)
+    wg, wu, wd = ([w[i] for w in W] for i in range(3))
+    R_cap = max(lay.R_cap, 32)
+    Xp = torch.zeros((R_cap, lay.d), dtype=torch.bfloat16, device=dev)
+    offsets = b.offsets[: G + 1]
+    B.feplb_permute(b.topk_ids, lay.E, p.groups, wl.X, lay.R_cap, Xp, offsets, b.row_src, b.inv, b.ws_permute)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(4242)
+    dYp = torch.empty((R_cap, lay.d), dtype=torch.float32, device=dev).normal_(generator=gen).to(torch.bfloat16)
+    st = FfnTrainingStep(R_cap, G, lay.d, lay.f, device=dev)
+    ms = time_phases(st, Xp, offsets, wg, wu, wd, dYp, reps=max(3, min(steps, 10)))
+    fl = 2.0 * p.R * lay.d * lay.f
+    return dict(ms=ms, flops_forward=3 * fl, flops_backward=6 * fl,
+                forward_tflops=3 * fl / (ms["forward_keeping_ab"] * 1e-3) / 1e12,
+                dgrad_tflops=3 * fl / (ms["dgrad"] * 1e-3) / 1e12,
+                wgrad_tflops=3 * fl / (ms["wgrad"] * 1e-3) / 1e12,
+                backward_tflops=6 * fl / (ms["backward"] * 1e-3) / 1e12,
+                backward_over_forward=ms["backward"] / ms["forward_keeping_ab"],
+                note="backward = weight transposes + dH GEMM with the SwiGLU derivative + dXp GEMM + three ragged "
+                     "weight-gradient GEMMs (fp32 out); upstream gradient synthetic; Xp materialised")
+
+
 def _copy_ms(layer):
     tl = layer.timeline
     if "copy_start" not in tl:
@@ -200,6 +232,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all", action="store_true", help="also time the other four workloads (reported under all_workloads)")
     ap.add_argument("--cpu-tokens", type=int, default=65536)
+    ap.add_argument("--no-training", action="store_true", help="skip the FFN training-step leg (forward keeping a|b, backward)")
     ap.add_argument("--yp-dtype", default="f32", choices=["f32", "bf16"],
                     help="type of the expert outputs Yp between the down GEMM and the combine")
     ap.add_argument("--early-static", action="store_true",
@@ -222,6 +255,11 @@ def main():
     cpu = None
     if not a.no_cpu_baseline:
         cpu = cpu_baseline(p, a.cpu_tokens)
+    training = None
+    if not a.no_training and res["f"] % 256 == 0 and res["d"] % 256 == 0:
+        training = training_leg(p, a.steps)
+        log(json.dumps(training))
+        torch.cuda.empty_cache()
     others = {}
     if a.all:
         p.wl.drop_weights()
@@ -258,6 +296,7 @@ def main():
                      "avg_launch_ms": res["gate_up_ms_per_launch"],
                      "flops_per_launch": 4.0 * res["d"] * res["f"] * res["R"] / res["gate_up_launches_per_step"]},
         "cpu_baseline": cpu,
+        "ffn_training_step": training,
         "detail": {k: res[k] for k in res if k not in ("workload",)},
         "device": _device_info(prop),
     }

@@ -1,0 +1,66 @@
+"""Buffers and call sequence of one training step of the grouped expert FFN (forward that keeps
+the gate/up products, then the backward pass; paper Section 3.2 reports both times).  Only
+allocation and sequencing live here: every step is a library call."""
+from __future__ import annotations
+
+from typing import Dict, Sequence
+
+import torch
+
+from . import binding as B
+
+
+class FfnTrainingStep:
+    """Holds what feplb_grouped_ffn (training form) and feplb_grouped_ffn_backward need for G
+    groups and up to R_cap permuted rows: H, a|b (turned into da|db by the backward), Yp, dXp,
+    the fp32 weight gradients, the transposed-weight scratch and the workspace."""
+
+    def __init__(self, R_cap: int, G: int, d: int, f: int, device="cuda:0", dxp_dtype=torch.float32):
+        dev = torch.device(device)
+        self.R_cap, self.G, self.d, self.f = max(R_cap, 32), G, d, f
+        R = self.R_cap
+        self.H = torch.empty((R, f), dtype=torch.bfloat16, device=dev)
+        self.AB = torch.empty((R, 2 * f), dtype=torch.bfloat16, device=dev)
+        self.Yp = torch.empty((R, d), dtype=torch.float32, device=dev)
+        self.dXp = torch.empty((R, d), dtype=dxp_dtype, device=dev)
+        self.dW_gate = [torch.empty((d, f), dtype=torch.float32, device=dev) for _ in range(G)]
+        self.dW_up = [torch.empty((d, f), dtype=torch.float32, device=dev) for _ in range(G)]
+        self.dW_down = [torch.empty((f, d), dtype=torch.float32, device=dev) for _ in range(G)]
+        self.WT = torch.empty((max(B.feplb_grouped_ffn_backward_wt_bytes(G, d, f), 16),), dtype=torch.uint8, device=dev)
+        self.ws = torch.empty((B.feplb_grouped_ffn_workspace_bytes(R, G),), dtype=torch.uint8, device=dev)
+
+    def forward(self, Xp, offsets, w_gate, w_up, w_down, stream=None):
+        """Xp bf16 [R_cap,d] (a materialised permuted copy, which the backward reads again)."""
+        B.feplb_grouped_ffn(Xp, offsets, 0, self.G, self.d, self.f, w_gate, w_up, w_down, self.H, self.Yp,
+                            ws=self.ws, stream=stream, AB=self.AB)
+        return self.Yp
+
+    def backward(self, Xp, offsets, w_gate, w_up, w_down, dYp, phases=B.BWD_ALL, stream=None):
+        """dYp bf16 [R_cap,d] -> dXp; the weight gradients land in dW_gate / dW_up / dW_down."""
+        B.feplb_grouped_ffn_backward(Xp, offsets, 0, self.G, self.d, self.f, w_gate, w_up, w_down, self.H, self.AB,
+                                     dYp, self.dXp, self.dW_gate, self.dW_up, self.dW_down, WT=self.WT,
+                                     phases=phases, ws=self.ws, stream=stream)
+        return self.dXp
+
+
+def time_phases(step: FfnTrainingStep, Xp, offsets, w_gate, w_up, w_down, dYp, reps: int = 5) -> Dict[str, float]:
+    """Milliseconds per call (HIP events on the default stream) of the training forward and of each
+    backward phase on its own, and of the whole backward in one call."""
+    e0, e1 = B.HipEvent(), B.HipEvent()
+
+    def timed(fn):
+        fn()
+        e0.record(None)
+        for _ in range(reps):
+            fn()
+        e1.record(None)
+        e1.synchronize()
+        return e0.elapsed_ms(e1) / reps
+
+    out = {"forward_keeping_ab": timed(lambda: step.forward(Xp, offsets, w_gate, w_up, w_down))}
+    step.forward(Xp, offsets, w_gate, w_up, w_down)
+    step.backward(Xp, offsets, w_gate, w_up, w_down, dYp)      # leaves tile table and transposes in place
+    for name, ph in (("transpose", B.BWD_TRANSPOSE), ("dgrad", B.BWD_DGRAD), ("wgrad", B.BWD_WGRAD),
+                     ("backward", B.BWD_ALL)):
+        out[name] = timed(lambda ph=ph: step.backward(Xp, offsets, w_gate, w_up, w_down, dYp, phases=ph))
+    return out
