@@ -138,22 +138,9 @@ def training_leg(p, steps):
     """Forward (keeping the gate/up products) and backward of the grouped FFN on the step's own
     groups and token rows, with a synthetic upstream gradient; reported beside the forward step,
     not part of `value`."""
-    import torch
-    from paper_2604_19654_amd import binding as B, runner
-    from paper_2604_19654_amd.training import FfnTrainingStep, time_phases
-    lay, b, wl = p.layer, p.layer.buf, p.wl
-    G = len(p.groups)
-    dev = wl.X.device
-    W = runner.group_weights(p)
-    wg, wu, wd = ([w[i] for w in W] for i in range(3))
-    R_cap = max(lay.R_cap, 32)
-    Xp = torch.zeros((R_cap, lay.d), dtype=torch.bfloat16, device=dev)
-    offsets = b.offsets[: G + 1]
-    B.feplb_permute(b.topk_ids, lay.E, p.groups, wl.X, lay.R_cap, Xp, offsets, b.row_src, b.inv, b.ws_permute)
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(4242)
-    dYp = torch.empty((R_cap, lay.d), dtype=torch.float32, device=dev).normal_(generator=gen).to(torch.bfloat16)
-    st = FfnTrainingStep(R_cap, G, lay.d, lay.f, device=dev)
+    from paper_2604_19654_amd.training import setup_from_prepared, time_phases
+    lay = p.layer
+    st, Xp, offsets, (wg, wu, wd), dYp = setup_from_prepared(p)
     ms = time_phases(st, Xp, offsets, wg, wu, wd, dYp, reps=max(3, min(steps, 10)))
     fl = 2.0 * p.R * lay.d * lay.f
     return dict(ms=ms, flops_forward=3 * fl, flops_backward=6 * fl,

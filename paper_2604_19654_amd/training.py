@@ -43,6 +43,27 @@ class FfnTrainingStep:
         return self.dXp
 
 
+def setup_from_prepared(p, seed: int = 4242, dxp_dtype=torch.float32):
+    """Training-step inputs on a workload that runner.step has already run once: the permuted copy
+    Xp of the step's own token rows (feplb_permute), its offsets, the groups' weights, a seeded
+    synthetic upstream gradient dYp ~ N(0,1) in bf16, and the buffers.
+    Returns (step, Xp, offsets, (w_gate, w_up, w_down), dYp)."""
+    from . import runner
+    lay, b, wl = p.layer, p.layer.buf, p.wl
+    G = len(p.groups)
+    dev = wl.X.device
+    W = runner.group_weights(p)
+    weights = tuple([w[i] for w in W] for i in range(3))
+    R_cap = max(lay.R_cap, 32)
+    Xp = torch.zeros((R_cap, lay.d), dtype=torch.bfloat16, device=dev)
+    offsets = b.offsets[: G + 1]
+    B.feplb_permute(b.topk_ids, lay.E, p.groups, wl.X, lay.R_cap, Xp, offsets, b.row_src, b.inv, b.ws_permute)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    dYp = torch.empty((R_cap, lay.d), dtype=torch.float32, device=dev).normal_(generator=gen).to(torch.bfloat16)
+    return FfnTrainingStep(R_cap, G, lay.d, lay.f, device=dev, dxp_dtype=dxp_dtype), Xp, offsets, weights, dYp
+
+
 def time_phases(step: FfnTrainingStep, Xp, offsets, w_gate, w_up, w_down, dYp, reps: int = 5) -> Dict[str, float]:
     """Milliseconds per call (HIP events on the default stream) of the training forward and of each
     backward phase on its own, and of the whole backward in one call."""

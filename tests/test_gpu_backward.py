@@ -213,3 +213,60 @@ def test_weight_gradients_add_up_over_a_split_of_the_rows():
         for one, two in zip(res[0][1], res[1][1]):
             scale = one.pow(2).mean().sqrt().item()
             assert (one - two).abs().max().item() <= 1e-5 * scale
+
+
+@pytest.mark.parametrize("name", ["C3", "C4"])
+def test_backward_at_full_size_on_sampled_outputs(name):
+    """The training step in the configuration bench.py times (the workload's own groups and token
+    rows, all groups in one call), checked where the oracle can follow: dXp on sampled rows (a row
+    needs only its own x and dy), weight gradients on sampled columns of sampled groups (a column
+    of dWg, dWu needs that column of da, db for every row of the group; a column of dWd needs that
+    column of dYp)."""
+    from paper_2604_19654_amd import runner
+    from paper_2604_19654_amd.training import setup_from_prepared
+    say(f"backward {name} at full size")
+    p = runner.prepare(name, DEV)
+    runner.step(p)
+    torch.cuda.synchronize()
+    st, Xp, offsets, (wg, wu, wd), dYp = setup_from_prepared(p)
+    st.forward(Xp, offsets, wg, wu, wd)
+    st.backward(Xp, offsets, wg, wu, wd, dYp)
+    torch.cuda.synchronize()
+    off = offsets.cpu().numpy()
+    sizes = np.diff(off)
+    say(f"  groups {sizes.tolist()}")
+    order = np.argsort(-sizes, kind="stable")
+    picked = [int(order[0]), int(order[min(2, len(order) - 1)])] + [int(g) for g in order if 0 < sizes[g] < 64][:2]
+    worst = np.zeros(4)
+    for g in dict.fromkeys(picked):
+        lo, hi = int(off[g]), int(off[g + 1])
+        if hi == lo:
+            continue
+        Wg, Wu, Wd = f64(wg[g]), f64(wu[g]), f64(wd[g])
+        rows = np.unique(np.concatenate([[lo, hi - 1], np.arange(lo, hi, max(1, (hi - lo) // 6))]))
+        dx_o = orc.ffn_rows_backward(f64(Xp[rows]), Wg, Wu, Wd, f64(dYp[rows]))[0]
+        e = check_rows(f64(st.dXp[rows]), dx_o, f"{name}: dXp rows of group {g}")
+        worst[:2] = np.maximum(worst[:2], e)
+        # columns j of the gate and up gradients (transposed: one row per sampled column)
+        cols = [0, st.f // 2 + 1, st.f - 1]
+        X64, dY64 = f64(Xp[lo:hi]), f64(dYp[lo:hi])
+        a, b = X64 @ Wg[:, cols], X64 @ Wu[:, cols]
+        sg = 1.0 / (1.0 + np.exp(-a))
+        dh = dY64 @ Wd[cols, :].T
+        da, db = dh * b * sg * (1.0 + a * (1.0 - sg)), dh * a * sg
+        e = check_rows(f64(st.dW_gate[g][:, cols]).T, (X64.T @ da).T, f"{name}: dW_gate[{g}] columns")
+        worst[2:] = np.maximum(worst[2:], e)
+        e = check_rows(f64(st.dW_up[g][:, cols]).T, (X64.T @ db).T, f"{name}: dW_up[{g}] columns")
+        worst[2:] = np.maximum(worst[2:], e)
+        # columns of the down gradient: dWd[:, c] = H^T dYp[:, c]
+        dcols = [0, st.d // 2 + 1, st.d - 1]
+        a_all, b_all = X64 @ Wg, X64 @ Wu
+        h = a_all / (1.0 + np.exp(-a_all)) * b_all
+        e = check_rows(f64(st.dW_down[g][:, dcols]).T, (h.T @ dY64[:, dcols]).T, f"{name}: dW_down[{g}] columns")
+        worst[2:] = np.maximum(worst[2:], e)
+        say(f"  group {g} ({hi - lo} rows) checked")
+    for g in np.nonzero(sizes == 0)[0][:3]:
+        assert not st.dW_gate[g].any() and not st.dW_up[g].any() and not st.dW_down[g].any()
+    say(f"  dXp rms {worst[0]:.5f} max {worst[1]:.5f}; weight gradients rms {worst[2]:.5f} max {worst[3]:.5f}")
+    p.wl.drop_weights()
+    torch.cuda.empty_cache()
