@@ -270,3 +270,33 @@ def test_backward_at_full_size_on_sampled_outputs(name):
     say(f"  dXp rms {worst[0]:.5f} max {worst[1]:.5f}; weight gradients rms {worst[2]:.5f} max {worst[3]:.5f}")
     p.wl.drop_weights()
     torch.cuda.empty_cache()
+
+
+def test_backward_of_a_split_group_range_equals_one_call():
+    # static range, then dynamic range, as the forward pass is launched; outputs must be the same bits
+    sizes = [300, 0, 45, 513, 70]
+    d, f, cut = 512, 256, 3
+    G = len(sizes)
+    off = torch.tensor(np.concatenate([[0], np.cumsum(sizes)]), dtype=torch.int32, device=DEV)
+    R = int(sum(sizes))
+    gen = torch.Generator().manual_seed(21)
+    Xp = torch.randn((R, d), generator=gen).to(torch.bfloat16).to(DEV)
+    dYp = torch.randn((R, d), generator=gen).to(torch.bfloat16).to(DEV)
+    W = [tuple(m.to(DEV) for m in w) for w in make_weights(G, d, f, 5)]
+    wl = [[w[i] for w in W] for i in range(3)]
+    res = []
+    for ranges in ([(0, G)], [(0, cut), (cut, G)]):
+        H = torch.zeros((R, f), dtype=torch.bfloat16, device=DEV)
+        AB = torch.zeros((R, 2 * f), dtype=torch.bfloat16, device=DEV)
+        Yp = torch.zeros((R, d), dtype=torch.float32, device=DEV)
+        dXp = torch.zeros((R, d), dtype=torch.float32, device=DEV)
+        dW = [[torch.full(s, 3.0, dtype=torch.float32, device=DEV) for _ in range(G)] for s in ((d, f), (d, f), (f, d))]
+        for g0, g1 in ranges:
+            fe.feplb_grouped_ffn(Xp, off, g0, g1, d, f, *wl, H, Yp, AB=AB)
+        for g0, g1 in ranges:
+            B.feplb_grouped_ffn_backward(Xp, off, g0, g1, d, f, *wl, H, AB, dYp, dXp, *dW)
+        torch.cuda.synchronize()
+        res.append((dXp, AB, dW))
+    assert torch.equal(res[0][0], res[1][0]) and torch.equal(res[0][1], res[1][1])
+    for mats_a, mats_b in zip(res[0][2], res[1][2]):
+        assert all(torch.equal(a, b) for a, b in zip(mats_a, mats_b))
