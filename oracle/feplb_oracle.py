@@ -23,6 +23,10 @@ What each function follows:
                     (Section 3.2 reports the layer's backward time beside the
                     forward one): chain rule on y = (silu(x Wg) * (x Wu)) Wd.
   combine           Section 2.3 (combine returns expert outputs to tokens).
+  combine_backward, permute_backward, route_topk_backward   the gradients of
+                    combine, gather_rows and route_topk's weights (selection held
+                    fixed), which with grouped_ffn_backward make up the layer's
+                    backward pass of Section 3.2.
   moe_token, moe_tokens   the layer's definition per token, no permutation.
   plan_whole        Section 2.3, the greedy whole-expert balancer.
   plan_overflow     NOT in the paper (which never splits an expert's batch):
@@ -199,6 +203,50 @@ def combine(Yp: np.ndarray, inv: np.ndarray, w: np.ndarray, T: int, k: int) -> n
         sel = np.nonzero(inv2[:, j] >= 0)[0]
         Y[sel] += w2[sel, j][:, None] * Yp[inv2[sel, j]]
     return Y
+
+
+def combine_backward(dY: np.ndarray, Yp: np.ndarray, inv: np.ndarray, w: np.ndarray, T: int, k: int):
+    """Gradients of L = sum(Y * dY), Y = combine(Yp, inv, w): every permuted row r
+    is slot (t, j) of exactly one token, so dYp[r,:] = w[t,j] * dY[t,:]; and
+    dw[t,j] = <dY[t,:], Yp[inv[t,j],:]> for a local slot, 0 for the others.
+    Returns (dYp [R,d], dw [T,k])."""
+    dY = np.asarray(dY, dtype=np.float64)
+    Yp = np.asarray(Yp, dtype=np.float64)
+    inv2 = np.asarray(inv).reshape(T, k)
+    w2 = np.asarray(w, dtype=np.float64).reshape(T, k)
+    dYp = np.zeros_like(Yp)
+    dw = np.zeros((T, k))
+    for j in range(k):
+        sel = np.nonzero(inv2[:, j] >= 0)[0]
+        rows = inv2[sel, j]
+        dYp[rows] = w2[sel, j][:, None] * dY[sel]
+        dw[sel, j] = np.einsum("ij,ij->i", dY[sel], Yp[rows])
+    return dYp, dw
+
+
+def permute_backward(dXp: np.ndarray, inv: np.ndarray, T: int, k: int) -> np.ndarray:
+    """Gradient of the row gather Xp[r,:] = X[row_src[r] // k, :]: token t receives the
+    sum of the gradients of the rows that are its copies, dX[t,:] = sum over local slots j
+    of dXp[inv[t,j],:]."""
+    return combine(np.asarray(dXp, dtype=np.float64), inv, np.ones((T, k)), T, k)
+
+
+def route_topk_backward(logits: np.ndarray, ids: np.ndarray, dw: np.ndarray) -> np.ndarray:
+    """Gradient of the k routing weights with respect to the logits, the selection held
+    fixed: the weights are the softmax of the k kept logits, so for a kept expert
+    dz[ids_j] = w_j (dw_j - sum_i w_i dw_i), and 0 for every other expert.
+    Returns dlogits [T,E] float64."""
+    z = np.asarray(logits, dtype=np.float64)
+    ids = np.asarray(ids)
+    dw = np.asarray(dw, dtype=np.float64)
+    T, E = z.shape
+    kept = np.take_along_axis(z, ids.astype(np.int64), axis=1)
+    ex = np.exp(kept - kept.max(axis=1, keepdims=True))
+    wk = ex / ex.sum(axis=1, keepdims=True)
+    inner = (wk * dw).sum(axis=1, keepdims=True)
+    out = np.zeros((T, E))
+    np.put_along_axis(out, ids.astype(np.int64), wk * (dw - inner), axis=1)
+    return out
 
 
 def moe_token(x_t: np.ndarray, ids_t, w_t, expert_weights: dict) -> np.ndarray:

@@ -425,6 +425,90 @@ def test_grouped_ffn_backward_uses_each_groups_own_rows_and_weights():
         assert abs(num - grads[g][which][idx]) < 1e-7
 
 
+# ---------------------------------------------------------------- layer backward: combine, permute, router
+def test_combine_backward_matches_central_differences_and_scalar_loops():
+    rng = np.random.default_rng(20)
+    T, k, d, R = 6, 3, 5, 9
+    inv = np.full(T * k, -1, dtype=np.int32)
+    slots = rng.permutation(T * k)[:R]
+    inv[slots] = rng.permutation(R)               # a bijection between R slots and R rows
+    Yp, dY, w = rng.normal(size=(R, d)), rng.normal(size=(T, d)), rng.uniform(0.1, 1.0, size=(T, k))
+    dYp, dw = orc.combine_backward(dY, Yp, inv, w, T, k)
+    # scalar loops straight from the definition
+    for t in range(T):
+        for j in range(k):
+            r = inv[t * k + j]
+            if r >= 0:
+                assert np.allclose(dYp[r], w[t, j] * dY[t], atol=1e-14)
+                assert abs(dw[t, j] - sum(dY[t, i] * Yp[r, i] for i in range(d))) < 1e-12
+            else:
+                assert dw[t, j] == 0.0
+    # central differences of L = sum(combine(...) * dY)
+    def loss(Yp_, w_):
+        return float(np.sum(orc.combine(Yp_, inv, w_, T, k) * dY))
+    eps = 1e-6
+    for idx in [(0, 0), (4, 2), (8, 4)]:
+        hi, lo = Yp.copy(), Yp.copy()
+        hi[idx] += eps; lo[idx] -= eps
+        assert abs((loss(hi, w) - loss(lo, w)) / (2 * eps) - dYp[idx]) < 1e-8
+    for t in range(T):
+        for j in range(k):
+            hi, lo = w.copy(), w.copy()
+            hi[t, j] += eps; lo[t, j] -= eps
+            assert abs((loss(Yp, hi) - loss(Yp, lo)) / (2 * eps) - dw[t, j]) < 1e-8
+
+
+def test_permute_backward_sums_the_copies_of_a_token():
+    rng = np.random.default_rng(21)
+    T, E, k, d = 12, 6, 3, 4
+    ids = np.stack([rng.permutation(E)[:k] for _ in range(T)]).astype(np.int32)
+    groups = [(0, 0, orc.INT32_MAX), (3, 0, orc.INT32_MAX), (5, 0, 2), (5, 2, orc.INT32_MAX)]
+    offsets, row_src, inv = orc.permute(ids, groups)
+    R = int(offsets[-1])
+    dXp = rng.normal(size=(R, d))
+    dX = orc.permute_backward(dXp, inv, T, k)
+    want = np.zeros((T, d))
+    for r in range(R):
+        want[row_src[r] // k] += dXp[r]
+    assert np.allclose(dX, want, atol=1e-14)
+    # adjoint of the gather: <gather(X), dXp> = <X, dX>
+    X = rng.normal(size=(T, d))
+    assert abs(np.sum(orc.gather_rows(X, row_src, k) * dXp) - np.sum(X * dX)) < 1e-12
+
+
+def test_route_backward_matches_central_differences_and_torch():
+    rng = np.random.default_rng(22)
+    T, E, k = 7, 9, 4
+    z = rng.normal(size=(T, E)).astype(np.float32)
+    ids, w, _ = orc.route_topk(z, k)
+    dw = rng.normal(size=(T, k))
+    dz = orc.route_topk_backward(z, ids, dw)
+    eps = 1e-3                                           # fp32 logits: a step the selection survives
+    z64 = z.astype(np.float64)
+    def weights_at(zz):
+        kept = np.take_along_axis(zz, ids.astype(np.int64), axis=1)
+        p = np.exp(zz - zz.max(axis=1, keepdims=True))
+        p /= p.sum(axis=1, keepdims=True)
+        pk = np.take_along_axis(p, ids.astype(np.int64), axis=1)
+        return pk / pk.sum(axis=1, keepdims=True)
+    assert np.allclose(weights_at(z64), w, atol=1e-12)    # same function as the forward's weights
+    for t, e in [(0, int(ids[0, 0])), (3, int(ids[3, 2])), (5, int(ids[5, 3])), (2, int(np.setdiff1d(np.arange(E), ids[2])[0]))]:
+        hi, lo = z64.copy(), z64.copy()
+        hi[t, e] += eps; lo[t, e] -= eps
+        num = np.sum((weights_at(hi) - weights_at(lo)) * dw) / (2 * eps)
+        assert abs(num - dz[t, e]) < 1e-6
+    # torch: softmax over the kept logits
+    tz = torch.from_numpy(z64).requires_grad_(True)
+    tw = torch.softmax(torch.gather(tz, 1, torch.from_numpy(ids.astype(np.int64))), dim=1)
+    tw.backward(torch.from_numpy(dw))
+    assert np.allclose(dz, tz.grad.numpy(), atol=1e-12)
+    # rows sum to zero (the weights sum to one), experts not kept get nothing
+    assert np.abs(dz.sum(axis=1)).max() < 1e-12
+    mask = np.ones((T, E), dtype=bool)
+    np.put_along_axis(mask, ids.astype(np.int64), False, axis=1)
+    assert not dz[mask].any()
+
+
 # ---------------------------------------------------------------- combine, end to end
 def small_layer(seed, T=40, E=8, k=2, d=12, f=10):
     rng = np.random.default_rng(seed)
