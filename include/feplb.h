@@ -258,6 +258,31 @@ int32_t feplb_unpermute_combine(const void* Yp, int32_t yp_dtype,
                                 int32_t T, int32_t k, int32_t d, void* Y,
                                 void* stream);
 
+/* ------------------------------------------------------------------ combine and router, backward
+ * Section 3.2 times the layer's backward pass; these are the gradients of its
+ * memory-bound steps (the grouped FFN's are above).  With dY[t,:] the gradient of the
+ * loss with respect to Y:
+ *     dYp[inv[t*k+j],:] = bf16( topk_w[t,j] * dY[t,:] )       for every local slot
+ *     dw[t,j] = sum_i dY[t,i] * Yp[inv[t*k+j],i]  (fp32)      0 for a slot that is not local
+ * and, the routing weights being the softmax of the k kept logits,
+ *     dlogits[t, topk_ids[t,j]] = w_j (dw_j - sum_i w_i dw_i)  0 for every expert not kept.
+ * The gradient of the row gather, dX[t,:] = sum over local slots of dXp[inv[t*k+j],:], is
+ * feplb_unpermute_combine(dXp, inv, unit weights).
+ *
+ *   dY      device, bf16 [T,d]
+ *   Yp      device, [R_cap,d] of yp_dtype, the expert outputs of the forward pass
+ *   dYp     device, bf16 [R_cap,d]  out (rows no slot refers to are left alone)
+ *   dw      device, fp32 [T,k]      out
+ *   dlogits device, fp32 [T,E]      out
+ * Limits: d % 8 == 0, k <= FEPLB_MAX_TOPK, E <= FEPLB_MAX_EXPERTS.
+ */
+int32_t feplb_combine_backward(const void* dY, const void* Yp, int32_t yp_dtype,
+                               const int32_t* inv, const float* topk_w,
+                               int32_t T, int32_t k, int32_t d, void* dYp, float* dw,
+                               void* stream);
+int32_t feplb_route_topk_backward(const int32_t* topk_ids, const float* topk_w, const float* dw,
+                                  int32_t T, int32_t E, int32_t k, float* dlogits, void* stream);
+
 /* ------------------------------------------------------------------ staging
  * Section 2.2 Phase 2 / Section 2.3: a dynamic expert's weights are copied into
  * a buffer of max_num_dyn x W_expert slots by a copy engine, off the compute

@@ -71,6 +71,8 @@ def lib():
                                                  vp, vp, vp, vp, i32, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
                                                  vp, sz, i32, vp, sz, vp]
         L.feplb_unpermute_combine.argtypes = [vp, i32, vp, vp, i32, i32, i32, vp, vp]
+        L.feplb_combine_backward.argtypes = [vp, vp, i32, vp, vp, i32, i32, i32, vp, vp, vp]
+        L.feplb_route_topk_backward.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
         L.feplb_stage_weights.argtypes = [vp, vp, sz, vp, vp]
         L.feplb_stream_wait.argtypes = [vp, vp]
         L.feplb_expert_bytes.argtypes = [i32, i32, i32]
@@ -78,7 +80,8 @@ def lib():
         L.feplb_plan.argtypes = [i32, i32, vp, vp, vp, vp, i64, i32, i32, C.POINTER(Move), i32,
                                  C.POINTER(i32), vp, vp, C.POINTER(i32)]
         for name in ("feplb_route_topk", "feplb_permute", "feplb_permute_append", "feplb_grouped_ffn", "feplb_grouped_ffn_train",
-                     "feplb_grouped_ffn_backward", "feplb_unpermute_combine",
+                     "feplb_grouped_ffn_backward", "feplb_unpermute_combine", "feplb_combine_backward",
+                     "feplb_route_topk_backward",
                      "feplb_stage_weights", "feplb_stream_wait", "feplb_plan"):
             getattr(L, name).restype = i32
         _LIB = L
@@ -310,6 +313,28 @@ def feplb_unpermute_combine(Yp, inv, topk_w, T, k, d, Y=None, stream=None):
     _check(lib().feplb_unpermute_combine(_ptr(Yp), yp_dtype, _ptr(inv), _ptr(topk_w), T, k, d, _ptr(Y),
                                          _stream(stream)), "feplb_unpermute_combine")
     return Y
+
+
+def feplb_combine_backward(dY, Yp, inv, topk_w, T, k, d, dYp, dw=None, stream=None):
+    """dY bf16 [T,d], Yp [R_cap,d] (fp32 or bf16) -> dYp bf16 [R_cap,d] (written in place), dw fp32 [T,k]."""
+    _need(dY, torch.bfloat16, "dY")
+    _need(dYp, torch.bfloat16, "dYp")
+    yp_dtype = {torch.float32: F32, torch.bfloat16: BF16}[Yp.dtype]
+    if dw is None:
+        dw = torch.empty((T, k), dtype=torch.float32, device=dY.device)
+    _check(lib().feplb_combine_backward(_ptr(dY), _ptr(Yp), yp_dtype, _ptr(inv), _ptr(topk_w), T, k, d,
+                                        _ptr(dYp), _ptr(dw), _stream(stream)), "feplb_combine_backward")
+    return dYp, dw
+
+
+def feplb_route_topk_backward(topk_ids, topk_w, dw, E, dlogits=None, stream=None):
+    """-> dlogits fp32 [T,E]."""
+    T, k = topk_ids.shape
+    if dlogits is None:
+        dlogits = torch.empty((T, E), dtype=torch.float32, device=topk_ids.device)
+    _check(lib().feplb_route_topk_backward(_ptr(topk_ids), _ptr(topk_w), _ptr(dw), T, E, k, _ptr(dlogits),
+                                           _stream(stream)), "feplb_route_topk_backward")
+    return dlogits
 
 
 def feplb_stage_weights(slot: torch.Tensor, src: torch.Tensor, side_stream, done_event: "HipEvent" = None):

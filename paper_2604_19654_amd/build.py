@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfeplb.so")
-SOURCES = ["host.cpp", "plan.cpp", "route.hip", "permute.hip", "ffn.hip", "ffn_backward.hip", "combine.hip"]
+SOURCES = ["host.cpp", "plan.cpp", "route.hip", "permute.hip", "ffn.hip", "ffn_backward.hip", "combine.hip", "layer_backward.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

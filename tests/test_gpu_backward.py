@@ -300,3 +300,68 @@ def test_backward_of_a_split_group_range_equals_one_call():
     assert torch.equal(res[0][0], res[1][0]) and torch.equal(res[0][1], res[1][1])
     for mats_a, mats_b in zip(res[0][2], res[1][2]):
         assert all(torch.equal(a, b) for a, b in zip(mats_a, mats_b))
+
+
+# ------------------------------------------------------------------ combine, row gather, router: backward
+@pytest.mark.parametrize("T,k,d,yp_dtype", [(100, 2, 256, torch.float32), (333, 8, 520, torch.float32),
+                                            (64, 4, 6144, torch.float32), (257, 8, 1024, torch.bfloat16), (5, 1, 8, torch.float32)])
+def test_combine_backward_parity(T, k, d, yp_dtype):
+    say(f"combine backward T={T} k={k} d={d} {yp_dtype}")
+    rng = np.random.default_rng(T + d)
+    n = T * k
+    R = int(0.6 * n)
+    inv = np.full(n, -1, dtype=np.int32)
+    slots = rng.permutation(n)[:R]
+    inv[slots] = rng.permutation(R)
+    gen = torch.Generator().manual_seed(T)
+    Yp = torch.randn((R + 5, d), generator=gen).to(yp_dtype)
+    dY = torch.randn((T, d), generator=gen).to(torch.bfloat16)
+    w = torch.rand((T, k), generator=gen) + 0.05
+    dYp = torch.full((R + 5, d), 512.0, dtype=torch.bfloat16, device=DEV)
+    _, dw = B.feplb_combine_backward(dY.to(DEV), Yp.to(DEV), torch.from_numpy(inv).to(DEV), w.to(DEV), T, k, d, dYp)
+    torch.cuda.synchronize()
+    dYp_o, dw_o = orc.combine_backward(f64(dY), f64(Yp)[:R], inv, f64(w), T, k)
+    # dYp: one rounding of an fp32 product to bf16
+    assert bf16_rounding_excess(f64(dYp)[:R], dYp_o) <= 1.0
+    assert (dYp[R:].float() == 512.0).all()
+    # dw: an fp32 dot product of d terms against the Cauchy-Schwarz scale of its two rows
+    scale = np.zeros((T, k))
+    inv2 = inv.reshape(T, k)
+    for j in range(k):
+        sel = inv2[:, j] >= 0
+        scale[sel, j] = np.linalg.norm(f64(dY)[sel], axis=1) * np.linalg.norm(f64(Yp)[inv2[sel, j]], axis=1)
+    err = np.abs(f64(dw) - dw_o)
+    assert (err <= 1e-5 * scale + 1e-30).all(), err.max()
+    assert not f64(dw)[inv2 < 0].any()
+
+
+def test_permute_backward_is_the_combine_with_unit_weights():
+    T, E, k, d = 300, 16, 4, 264
+    rng = np.random.default_rng(8)
+    ids = np.stack([rng.permutation(E)[:k] for _ in range(T)]).astype(np.int32)
+    groups = [(e, 0, B.ORD_MAX) for e in (1, 4, 9, 15)]
+    X = torch.zeros((T, d), dtype=torch.bfloat16, device=DEV)
+    R_cap = T * k
+    _, offsets, row_src, inv = B.feplb_permute(torch.from_numpy(ids).to(DEV), E, groups, None, R_cap)
+    torch.cuda.synchronize()
+    R = int(offsets[-1].item())
+    dXp = torch.randn((R_cap, d), generator=torch.Generator().manual_seed(2)).to(DEV)
+    dX = B.feplb_unpermute_combine(dXp, inv, torch.ones((T, k), device=DEV), T, k, d)
+    torch.cuda.synchronize()
+    want = orc.permute_backward(f64(dXp)[:R], inv.cpu().numpy(), T, k)
+    # fp32 sums of at most k rows, one rounding to bf16: every element within a bf16 step
+    assert bf16_rounding_excess(f64(dX), want) <= 1.0
+
+
+@pytest.mark.parametrize("T,E,k", [(200, 8, 2), (1000, 128, 8), (77, 5, 5), (3, 1024, 32)])
+def test_route_backward_parity(T, E, k):
+    say(f"route backward T={T} E={E} k={k}")
+    gen = torch.Generator().manual_seed(T + E)
+    logits = torch.randn((T, E), generator=gen)
+    dw = torch.randn((T, k), generator=gen)
+    ids, w, _ = B.feplb_route_topk(logits.to(DEV), k)
+    dz = B.feplb_route_topk_backward(ids, w, dw.to(DEV), E)
+    torch.cuda.synchronize()
+    want = orc.route_topk_backward(logits.numpy(), ids.cpu().numpy(), f64(dw))
+    assert np.abs(f64(dz) - want).max() <= 2e-6 * max(1.0, float(dw.abs().max()))
+    assert np.array_equal(f64(dz) != 0, want != 0) or np.abs(f64(dz) - want).max() < 1e-12
