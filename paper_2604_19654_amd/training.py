@@ -64,6 +64,41 @@ def setup_from_prepared(p, seed: int = 4242, dxp_dtype=torch.float32):
     return FfnTrainingStep(R_cap, G, lay.d, lay.f, device=dev, dxp_dtype=dxp_dtype), Xp, offsets, weights, dYp
 
 
+class LayerBackward:
+    """The layer's backward pass behind a training forward on the same buffers (FfnTrainingStep.forward
+    on the permuted copy, then the combine): dY [T,d] -> dYp (combine backward, which also yields the
+    routing weights' gradient) -> dXp and the weight gradients (FFN backward) -> dX (row gather backward:
+    the combine with unit weights) and dlogits (router backward).  Sequencing and buffers only."""
+
+    def __init__(self, T: int, E: int, k: int, step: FfnTrainingStep):
+        dev = step.H.device
+        self.T, self.E, self.k, self.step = T, E, k, step
+        self.dYp = torch.empty((step.R_cap, step.d), dtype=torch.bfloat16, device=dev)
+        self.dw = torch.empty((T, k), dtype=torch.float32, device=dev)
+        self.ones = torch.ones((T, k), dtype=torch.float32, device=dev)
+        self.dX = torch.empty((T, step.d), dtype=torch.bfloat16, device=dev)
+        self.dlogits = torch.empty((T, E), dtype=torch.float32, device=dev)
+
+    def run(self, dY, Xp, offsets, weights, topk_ids, topk_w, inv, events=None):
+        """events: optional dict that receives HipEvents recorded between the steps."""
+        st = self.step
+        wg, wu, wd = weights
+
+        def mark(name):
+            if events is not None:
+                events.setdefault(name, B.HipEvent()).record(None)
+        mark("start")
+        B.feplb_combine_backward(dY, st.Yp, inv, topk_w, self.T, self.k, st.d, self.dYp, self.dw)
+        mark("combine_backward")
+        st.backward(Xp, offsets, wg, wu, wd, self.dYp)
+        mark("ffn_backward")
+        B.feplb_unpermute_combine(st.dXp, inv, self.ones, self.T, self.k, st.d, Y=self.dX)
+        mark("gather_backward")
+        B.feplb_route_topk_backward(topk_ids, topk_w, self.dw, self.E, self.dlogits)
+        mark("route_backward")
+        return self.dX, self.dlogits
+
+
 def time_phases(step: FfnTrainingStep, Xp, offsets, w_gate, w_up, w_down, dYp, reps: int = 5) -> Dict[str, float]:
     """Milliseconds per call (HIP events on the default stream) of the training forward and of each
     backward phase on its own, and of the whole backward in one call."""

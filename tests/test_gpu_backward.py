@@ -365,3 +365,57 @@ def test_route_backward_parity(T, E, k):
     want = orc.route_topk_backward(logits.numpy(), ids.cpu().numpy(), f64(dw))
     assert np.abs(f64(dz) - want).max() <= 2e-6 * max(1.0, float(dw.abs().max()))
     assert np.array_equal(f64(dz) != 0, want != 0) or np.abs(f64(dz) - want).max() < 1e-12
+
+
+# ------------------------------------------------------------------ the layer's backward pass, end to end
+LAYER_CASES = {
+    "C1": {},                                     # the tiny workload at its full size (f=512, d=256)
+    "C3": dict(T=2048, d=512, f=256),             # hot groups of ~2k rows, several empty groups
+    "C5": dict(T=2048, d=768, f=256),             # 32 groups
+}
+
+
+@pytest.mark.parametrize("name", list(LAYER_CASES))
+def test_layer_backward_parity(name):
+    """Route, permute, training forward and combine, then the whole backward chain, against the
+    oracle's chain on the same inputs: dX and the weight gradients per row, dlogits over all tokens."""
+    from paper_2604_19654_amd import runner
+    from paper_2604_19654_amd.training import setup_from_prepared, LayerBackward
+    say(f"layer backward {name} {LAYER_CASES[name]}")
+    p = runner.prepare(name, DEV, **LAYER_CASES[name])
+    runner.step(p)
+    torch.cuda.synchronize()
+    wl, b = p.wl, p.layer.buf
+    st, Xp, offsets, weights, _ = setup_from_prepared(p)
+    st.forward(Xp, offsets, *weights)
+    dY = torch.randn((wl.T, wl.d), generator=torch.Generator().manual_seed(17)).to(torch.bfloat16)
+    lb = LayerBackward(wl.T, wl.E, wl.k, st)
+    dX, dlogits = lb.run(dY.to(DEV), Xp, offsets, weights, b.topk_ids, b.topk_w, b.inv)
+    torch.cuda.synchronize()
+
+    ids, w, _ = orc.route_topk(wl.logits.cpu().numpy(), wl.k)
+    groups = [(int(e), 0, orc.INT32_MAX) for e in wl.local_experts()]
+    off_o, row_src, inv = orc.permute(ids, groups)
+    R = int(off_o[-1])
+    Wo = [tuple(f64(m) for m in wl.expert_weights(e)) for (e, _lo, _hi) in groups]
+    Xp_o = orc.gather_rows(f64(wl.X), row_src, wl.k)
+    _, Yp_o = orc.grouped_ffn(Xp_o, off_o, Wo)
+    dYp_o, dw_o = orc.combine_backward(f64(dY), Yp_o, inv, w, wl.T, wl.k)
+    dXp_o, grads_o = orc.grouped_ffn_backward(Xp_o, off_o, Wo, dYp_o)
+    dX_o = orc.permute_backward(dXp_o, inv, wl.T, wl.k)
+    dz_o = orc.route_topk_backward(wl.logits.cpu().numpy(), ids, dw_o)
+
+    local = (inv.reshape(wl.T, wl.k) >= 0).any(axis=1)
+    assert not f64(dX)[~local].any()                     # tokens without a local slot get no gradient
+    ex = check_rows(f64(dX)[local], dX_o[local], "dX")
+    r = dict(offsets=off_o, dW=list(zip(st.dW_gate, st.dW_up, st.dW_down)))
+    ew = check_weight_grads(r, grads_o, "layer")
+    # dlogits: the dot products behind dw cancel heavily, so single entries can be off by much more
+    # than their own size; the bar is on the root mean square over all tokens
+    dz = f64(dlogits)
+    rel = np.sqrt(((dz - dz_o) ** 2).mean()) / np.sqrt((dz_o ** 2).mean())
+    say(f"  R={R} dX rms {ex[0]:.5f} max {ex[1]:.5f}; weight gradients rms {ew[0]:.5f} max {ew[1]:.5f}; dlogits rms {rel:.5f}")
+    assert rel <= BWD_RMS_TOL
+    assert np.array_equal(dz != 0, dz_o != 0) or np.abs(dz - dz_o)[(dz != 0) != (dz_o != 0)].max() < 1e-12
+    p.wl.drop_weights()
+    torch.cuda.empty_cache()
