@@ -138,12 +138,34 @@ def training_leg(p, steps):
     """Forward (keeping the gate/up products) and backward of the grouped FFN on the step's own
     groups and token rows, with a synthetic upstream gradient; reported beside the forward step,
     not part of `value`."""
-    from paper_2604_19654_amd.training import setup_from_prepared, time_phases
-    lay = p.layer
+    import torch
+    from paper_2604_19654_amd.training import setup_from_prepared, time_phases, LayerBackward
+    lay, b, wl = p.layer, p.layer.buf, p.wl
     st, Xp, offsets, (wg, wu, wd), dYp = setup_from_prepared(p)
-    ms = time_phases(st, Xp, offsets, wg, wu, wd, dYp, reps=max(3, min(steps, 10)))
+    reps = max(3, min(steps, 10))
+    ms = time_phases(st, Xp, offsets, wg, wu, wd, dYp, reps=reps)
+    # the layer's whole backward chain behind that forward: combine, FFN, row gather, router
+    gen = torch.Generator(device=wl.X.device)
+    gen.manual_seed(4243)
+    dY = torch.empty((wl.T, lay.d), dtype=torch.float32, device=wl.X.device).normal_(generator=gen).to(torch.bfloat16)
+    lb = LayerBackward(wl.T, wl.E, wl.k, st)
+    ev, chain = {}, {}
+    st.forward(Xp, offsets, wg, wu, wd)
+    lb.run(dY, Xp, offsets, (wg, wu, wd), b.topk_ids, b.topk_w, b.inv, events=ev)
+    names = ["start", "combine_backward", "ffn_backward", "gather_backward", "route_backward"]
+    for _ in range(reps):
+        lb.run(dY, Xp, offsets, (wg, wu, wd), b.topk_ids, b.topk_w, b.inv, events=ev)
+        ev["route_backward"].synchronize()
+        for a_, b_ in zip(names[:-1], names[1:]):
+            chain[b_] = chain.get(b_, 0.0) + ev[a_].elapsed_ms(ev[b_]) / reps
+    chain["total"] = sum(chain.values())
+    R, d, T, k = p.R, lay.d, wl.T, wl.k
+    yp_bytes = st.Yp.element_size()
     fl = 2.0 * p.R * lay.d * lay.f
-    return dict(ms=ms, flops_forward=3 * fl, flops_backward=6 * fl,
+    return dict(ms=ms, layer_backward_ms=chain,
+                combine_backward_gbps=(T * d * 2 + R * d * yp_bytes + R * d * 2 + T * k * 12) / (chain["combine_backward"] * 1e-3) / 1e9,
+                gather_backward_gbps=(R * d * st.dXp.element_size() + T * d * 2 + T * k * 8) / (chain["gather_backward"] * 1e-3) / 1e9,
+                flops_forward=3 * fl, flops_backward=6 * fl,
                 forward_tflops=3 * fl / (ms["forward_keeping_ab"] * 1e-3) / 1e12,
                 dgrad_tflops=3 * fl / (ms["dgrad"] * 1e-3) / 1e12,
                 wgrad_tflops=3 * fl / (ms["wgrad"] * 1e-3) / 1e12,
