@@ -51,6 +51,28 @@ def test_argument_validation_happens_before_any_device_work():
     assert rc == -2
     rc = L.feplb_grouped_ffn(None, None, 0, 0, None, 0, 1, 128, 256, 128, None, None, None, None, None, 0, 0, None, 0, None)
     assert rc == -1
+    # backward entry points: shape, phase, dtype and capacity checks come before any pointer is used
+    bw = L.feplb_grouped_ffn_backward
+    assert bw(None, None, 0, 1, 64, 256, 128, None, None, None, None, None, None, None, 0, None, None, None,
+              None, 0, 15, None, 0, None) == -2                                          # f % 256
+    assert bw(None, None, 0, 1, 64, 256, 256, None, None, None, None, None, None, None, 0, None, None, None,
+              None, 0, 0, None, 0, None) == -1                                           # no phase
+    assert bw(None, None, 0, 1, 64, 256, 256, None, None, None, None, None, None, None, 5, None, None, None,
+              None, 0, 15, None, 0, None) == -1                                          # dXp type
+    assert bw(None, None, 0, 1, 16, 256, 256, None, None, None, None, None, None, None, 0, None, None, None,
+              None, 0, 8, None, 0, None) == -2 and b"R_cap >= 32" in L.feplb_last_error()
+    assert bw(None, None, 0, 200, 64, 256, 256, None, None, None, None, None, None, None, 0, None, None, None,
+              None, 0, 15, None, 0, None) == -2                                          # more groups than the limit
+    assert bw(None, None, 3, 3, 64, 256, 256, None, None, None, None, None, None, None, 0, None, None, None,
+              None, 0, 15, None, 0, None) == 0                                           # empty range: nothing to do
+    assert fe.binding.feplb_grouped_ffn_backward_wt_bytes(20, 6144, 2048) == 20 * 72 * 2**20   # one transposed copy of every expert
+    assert L.feplb_grouped_ffn_train(None, None, 0, 0, None, 0, 1, 128, 256, 128, None, None, None, None, None, None,
+                                     0, 7, None, 0, None) == -1                          # keeping a | b needs the AB buffer
+    assert L.feplb_combine_backward(None, None, 0, None, None, 4, 2, 12, None, None, None) == -2     # d % 8
+    assert L.feplb_combine_backward(None, None, 9, None, None, 4, 2, 16, None, None, None) == -1     # dtype
+    assert L.feplb_combine_backward(None, None, 0, None, None, 0, 2, 16, None, None, None) == 0      # no tokens
+    assert L.feplb_route_topk_backward(None, None, None, 4, 4, 5, None, None) == -2                  # k > E
+    assert L.feplb_route_topk_backward(None, None, None, 4, 8, 2, None, None) == -1                  # null buffers
     assert fe.feplb_permute_workspace_bytes(1024, 8, 128, 20) > 0
     assert fe.feplb_grouped_ffn_workspace_bytes(4096, 20) >= (4096 // 256 + 20) * 16   # one entry per 256-row tile
 
