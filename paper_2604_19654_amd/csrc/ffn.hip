@@ -6,6 +6,13 @@
 //   gate_up : H[r,:]  = bf16( silu(x_r Wg[g]) * (x_r Wu[g]) ),  x_r = Xp[r,:] or, with row_src,
 //             the token row X[row_src[r] / k, :] gathered while it is loaded
 //   down    : Yp[r,:] = H[r,:] Wd[g]
+// The same kernel serves training (Section 3.2 times the backward pass as well): the gate_up
+// form can also keep the two products a = x Wg, b = x Wu (bf16) for the backward pass, and two
+// more forms give the input gradients,
+//   dswiglu : dH = dYp Wd^T, then [da | db] = dH * d(silu(a) b)/d(a, b), written over [a | b]
+//   plain   : dXp = [da | db] [Wg^T; Wu^T]   (the down form with another K)
+// with the transposed weights made by a small kernel of ffn_backward.hip, which also holds the
+// ragged weight-gradient GEMM.
 // A small schedule kernel turns offsets[] (device memory, ragged, possibly
 // empty groups) into a table of row tiles; the GEMM grid covers an upper bound
 // of tiles and surplus blocks leave at once, so the host never needs R.
