@@ -419,3 +419,22 @@ def test_layer_backward_parity(name):
     assert np.array_equal(dz != 0, dz_o != 0) or np.abs(dz - dz_o)[(dz != 0) != (dz_o != 0)].max() < 1e-12
     p.wl.drop_weights()
     torch.cuda.empty_cache()
+
+
+def test_grouped_ffn_backward_over_random_shapes():
+    # random group counts and sizes (empty groups, single rows, sizes around the 32-row window and
+    # the 256-row tile), random widths: every case against the oracle
+    rng = np.random.default_rng(2024)
+    pool = [0, 0, 1, 2, 31, 32, 33, 63, 64, 65, 100, 255, 256, 257, 300, 511, 513]
+    for case in range(8):
+        G = int(rng.integers(1, 9))
+        sizes = [int(rng.choice(pool)) for _ in range(G)]
+        d = int(rng.choice([256, 512, 768]))
+        f = int(rng.choice([256, 512]))
+        say(f"ffn backward random case {case}: sizes={sizes} d={d} f={f}")
+        r = run_forward_backward(sizes, d, f, torch.float32, pad=int(rng.integers(0, 40)), seed=100 + case)
+        (dXp_o, grads_o), _ = oracle_backward(r)
+        if r["R"]:
+            check_rows(f64(r["dXp"])[:r["R"]], dXp_o, f"case {case}: dXp")
+        check_weight_grads(r, grads_o, f"case {case}")
+        assert (r["dXp"][r["R"]:].float() == 512.0).all()
