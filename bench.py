@@ -295,7 +295,7 @@ def main():
                    "yp_dtype": a.yp_dtype, "x_rows": "permuted copy" if a.materialize_xp else "gathered by the gate/up GEMM",
                    "schedule": ("static experts launched before the plan" if a.early_static else "plan first") if a.workload == "C4" else None,
                    "staging_source": a.source if a.workload == "C4" else None},
-        "roofline": {"kernel": "grouped_gemm_kernel<0,true> (gate/up GEMM + SwiGLU)", "bound": "mfma",
+        "roofline": {"kernel": "grouped_gemm_kernel<0,true,false> (gate/up GEMM + SwiGLU)", "bound": "mfma",
                      "achieved": up_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": up_tflops / MFMA_BF16_PEAK_TFLOPS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(a.workload),
