@@ -78,6 +78,32 @@ class FfnTimer:
         self.wd = [w((f, d)) for _ in range(max_groups)]
         self.e0, self.e1 = B.HipEvent(), B.HipEvent()
 
+    def time_train_ms(self, sizes: Sequence[int], reps: int = 2):
+        """(forward keeping the gate/up products, backward) of one share, in ms."""
+        from .training import FfnTrainingStep
+        G = len(sizes)
+        if G == 0 or sum(sizes) == 0:
+            return 0.0, 0.0
+        if G > self.max_groups or sum(sizes) > self.max_rows:
+            raise B.FeplbError("FfnTimer: share larger than the buffers")
+        if getattr(self, "_train", None) is None or self._train.G != G:
+            self._train = None       # buffers of the previous group count go first
+            self._train = FfnTrainingStep(self.max_rows, G, self.d, self.f, device=self.Xp.device)
+            self._dYp = self.Xp.flip(0)
+        st = self._train
+        off = torch.tensor(np.concatenate([[0], np.cumsum(sizes)]), dtype=torch.int32, device=self.Xp.device)
+        w = (self.wg[:G], self.wu[:G], self.wd[:G])
+        out = []
+        for fn in (lambda: st.forward(self.Xp, off, *w), lambda: st.backward(self.Xp, off, *w, self._dYp)):
+            fn()
+            self.e0.record(None)
+            for _ in range(reps):
+                fn()
+            self.e1.record(None)
+            self.e1.synchronize()
+            out.append(self.e0.elapsed_ms(self.e1) / reps)
+        return out[0], out[1]
+
     def time_ms(self, sizes: Sequence[int], reps: int = 3) -> float:
         G = len(sizes)
         if G == 0 or sum(sizes) == 0:
@@ -97,12 +123,13 @@ class FfnTimer:
 
 def study(P: int, dyn_list: Sequence[int], n_batches: int, tokens_per_rank: int = 16384, E: int = 128,
           k: int = 8, d: int = 6144, f: int = 2048, tau: int = 0, seed0: int = 5000, gemm_dyn: int = 4,
-          device="cuda:0", with_gemm: bool = True) -> Dict:
+          device="cuda:0", with_gemm: bool = True, with_backward: bool = False) -> Dict:
     """Mean token straggler before / after the plan for every dyn in dyn_list, and (for
     dyn = gemm_dyn) the mean GEMM straggler before / after, over n_batches micro-batches."""
     T = P * tokens_per_rank
     tok = {"before": [], **{f"dyn{n}": [] for n in dyn_list}}
     gemm = {"before": [], "after": []}
+    layer = {"fwd_before": [], "bwd_before": [], "fwd_after": [], "bwd_after": []}
     timer = None
     for b in range(n_batches):
         # token rows are not needed: the smallest legal widths keep the generator cheap
@@ -125,6 +152,12 @@ def study(P: int, dyn_list: Sequence[int], n_batches: int, tokens_per_rank: int 
                     timer = FfnTimer(d, f, max_rows=int(counts.sum()), max_groups=min(E, B.MAX_GROUPS), device=device)
                 gemm["before"].append(straggler([timer.time_ms(s) for s in shares_before]))
                 gemm["after"].append(straggler([timer.time_ms(s) for s in shares_after]))
+                if with_backward:
+                    # the layer waits for its slowest rank (Section 3.2): max over the ranks' times
+                    for key, shares in (("before", shares_before), ("after", shares_after)):
+                        times = [timer.time_train_ms(s) for s in shares]
+                        layer["fwd_" + key].append(max(t[0] for t in times))
+                        layer["bwd_" + key].append(max(t[1] for t in times))
     out = {"P": P, "batches": n_batches, "tokens_per_rank": tokens_per_rank, "E": E, "k": k, "tau": tau,
            "token_straggler": {key: float(np.mean(v)) for key, v in tok.items()}}
     base = out["token_straggler"]["before"]
@@ -133,6 +166,8 @@ def study(P: int, dyn_list: Sequence[int], n_batches: int, tokens_per_rank: int 
         gb, ga = float(np.mean(gemm["before"])), float(np.mean(gemm["after"]))
         out["gemm_straggler_ms"] = {"before": gb, f"dyn{gemm_dyn}": ga, "d": d, "f": f}
         out["gemm_reduction_pct"] = 100.0 * (1.0 - ga / gb) if gb > 0 else 0.0
+    if layer["fwd_before"]:
+        out["slowest_rank_ffn_ms"] = {key: float(np.mean(v)) for key, v in layer.items()}
     return out
 
 
@@ -146,11 +181,13 @@ def main():
     ap.add_argument("--f", type=int, default=2048)
     ap.add_argument("--tau", type=int, default=0)
     ap.add_argument("--no-gemm", action="store_true")
+    ap.add_argument("--backward", action="store_true",
+                    help="also time every rank's FFN training step (forward keeping a|b, backward) and report the slowest rank's times before and after the plan")
     a = ap.parse_args()
     B.lib()
     rows = []
     for P in a.ep:
-        r = study(P, a.dyn, a.batches, a.tokens_per_rank, d=a.d, f=a.f, tau=a.tau, with_gemm=not a.no_gemm)
+        r = study(P, a.dyn, a.batches, a.tokens_per_rank, d=a.d, f=a.f, tau=a.tau, with_gemm=not a.no_gemm, with_backward=a.backward)
         rows.append(r)
         print(json.dumps(r), flush=True)
     print("\n| EP | token straggler before | " + " | ".join(f"dyn={n}" for n in a.dyn) + " | GEMM straggler before (ms) | dyn=4 (ms) |")
@@ -161,6 +198,13 @@ def main():
         g = r.get("gemm_straggler_ms")
         gcells = [f"{g['before']:.3f}", f"{g['dyn4']:.3f} (-{r['gemm_reduction_pct']:.0f}%)"] if g and "dyn4" in g else ["-", "-"]
         print(f"| {r['P']} | {t['before']:.0f} | " + " | ".join(cells) + " | " + " | ".join(gcells) + " |")
+    if a.backward:
+        print("\n| EP | slowest rank's FFN forward / backward before (ms) | after, dyn=4 (ms) |")
+        print("|---|---|---|")
+        for r in rows:
+            m = r.get("slowest_rank_ffn_ms")
+            if m:
+                print(f"| {r['P']} | {m['fwd_before']:.2f} / {m['bwd_before']:.2f} | {m['fwd_after']:.2f} / {m['bwd_after']:.2f} |")
 
 
 if __name__ == "__main__":
