@@ -215,7 +215,7 @@ def test_weight_gradients_add_up_over_a_split_of_the_rows():
             assert (one - two).abs().max().item() <= 1e-5 * scale
 
 
-@pytest.mark.parametrize("name", ["C3", "C4"])
+@pytest.mark.parametrize("name", ["C3", "C4", "C5"])
 def test_backward_at_full_size_on_sampled_outputs(name):
     """The training step in the configuration bench.py times (the workload's own groups and token
     rows, all groups in one call), checked where the oracle can follow: dXp on sampled rows (a row
