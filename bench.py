@@ -95,6 +95,20 @@ def time_workload(name, steps, warmup, source_kind="device", fused_gather=True, 
         combine_gbps=(R * d * yp_bytes + T * d * 2 + T * k * 8) / (ms["combine"] * 1e-3) / 1e9,
         route_gbps=(T * wl.E * 4 + T * k * 8) / (ms["route"] * 1e-3) / 1e9,
     )
+    if not p.rebalanced:
+        # the same step recorded once into a HIP graph and replayed: one submission instead of
+        # about ten launches (a share without replicas has no host round trip inside the step)
+        graph = layer.capture_forward(wl.logits, wl.X, p.groups, p.weights)
+        for _ in range(warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        res["graph_replay_ms_per_step"] = (time.perf_counter() - t0) * 1e3 / steps
+        res["ffn_tflops_step_graph_replay"] = ffn_flops / (res["graph_replay_ms_per_step"] * 1e-3) / 1e12
+        del graph
     res["fused_gather"] = fused_gather
     res["yp_dtype"] = yp_dtype
     # the permute step with its row gather (X -> Xp), timed on its own when the step's GEMM gathers the rows itself
@@ -281,7 +295,7 @@ def main():
             log(json.dumps(r))
             others[name] = {k: r[k] for k in ("R", "ms_per_step", "ffn_tflops_kernels", "pct_mfma_peak_ffn_kernels",
                                               "gate_up_tflops", "down_tflops", "combine_gbps", "route_gbps",
-                                              "permute_gbps")}
+                                              "permute_gbps", "graph_replay_ms_per_step") if k in r}
             q.wl.drop_weights()
             del q
             torch.cuda.empty_cache()

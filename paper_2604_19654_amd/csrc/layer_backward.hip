@@ -7,21 +7,16 @@
 //             dw[t,j] = <dY[t,:], Yp[inv[t,j],:]>, 0 for a slot that is not local
 //   router:   w = softmax of the k kept logits      =>  dz[ids_j] = w_j (dw_j - sum_i w_i dw_i)
 #include "common.h"
+#include "gemm_device.h"
 
 namespace {
+using feplb::dev::pack_bf16;
 
 constexpr int WAVES = 4;
 constexpr int BLOCK = WAVES * 64;
 
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+using feplb::dev::u32x4;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-  typedef float f32x2 __attribute__((ext_vector_type(2)));
-  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-  const f32x2 v = {lo, hi};
-  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
-}
 
 // One wavefront per token; its local slots are walked in ascending j.  A lane owns 16 bytes of
 // the gradient row per step (8 bf16 values): it reads them from dY[t,:] (re-read per local slot,

@@ -131,6 +131,18 @@ class RankLayer:
         self._mark("combined", mark)
         return b.Y
 
+    def capture_forward(self, logits, X, groups: Sequence[Tuple[int, int, int]], weights: Sequence[Tuple]):
+        """Records one `forward` on these very buffers into a HIP graph and returns it; `replay()`
+        then re-runs the step (router to combine, about ten launches) as one submission, which is
+        what the small workloads need: their step is as long as its launch gaps.  The step has no
+        host round trip and the library launches nothing but kernels (no memset nodes).  The
+        graph reads `logits`, `X` and the weights where they are now and writes `self.buf.Y`."""
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            self.forward(logits, X, groups, weights, mark=False)
+        return g
+
     # -- rebalanced layer: static experts + replicas of the hottest foreign experts
     def forward_rebalanced_early_static(self, logits, X, P, owner, dyn_flag, slots, this_rank,
                                         static_weights: Dict[int, Tuple],

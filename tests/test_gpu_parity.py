@@ -563,3 +563,29 @@ def test_misaligned_and_small_workspace_are_refused():
         H = torch.zeros((8, 128), dtype=torch.bfloat16, device=DEV)
         fe.feplb_grouped_ffn(X[:8], torch.zeros(2, dtype=torch.int32, device=DEV), 0, 1, 64, 128,
                              [X], [X], [X], H, torch.zeros((8, 64), device=DEV))
+
+
+def test_graph_replay_of_the_static_step_equals_the_eager_step():
+    # several replays, each after new inputs were copied into the captured buffers and with eager
+    # work and synchronisations in between; every replay against the eager step on the same inputs
+    p = runner.prepare("C2", DEV, T=1536, d=512, f=384)
+    wl, lay = p.wl, p.layer
+    runner.step(p)
+    torch.cuda.synchronize()
+    graph = lay.capture_forward(wl.logits, wl.X, p.groups, p.weights)
+    gen = torch.Generator(device=DEV)
+    for it in range(4):
+        gen.manual_seed(90 + it)
+        wl.logits.copy_(torch.empty_like(wl.logits).normal_(generator=gen) * (1.0 + it))
+        wl.X.copy_(torch.empty(wl.X.shape, dtype=torch.float32, device=DEV).normal_(generator=gen).to(torch.bfloat16))
+        torch.cuda.synchronize()
+        eager = runner.step(p).clone()
+        ids_eager = lay.buf.topk_ids.clone()
+        torch.cuda.synchronize()
+        lay.buf.Y.zero_()
+        lay.buf.topk_ids.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(lay.buf.topk_ids, ids_eager), f"replay {it}: routing differs"
+        assert torch.equal(lay.buf.Y, eager), f"replay {it}: output differs"
+        (lay.buf.Y.float().sum() + wl.X.float().sum()).item()        # eager library work between replays
