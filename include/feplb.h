@@ -210,7 +210,10 @@ int32_t feplb_grouped_ffn(const void* Xp, const int32_t* row_src, int32_t T, int
  *           in the forward call; may be skipped when ws still holds the forward call's
  *           table for the same range), FEPLB_BWD_TRANSPOSE, FEPLB_BWD_DGRAD (needs
  *           the table and WT), FEPLB_BWD_WGRAD.  WGRAD for the gate and up matrices
- *           needs da | db, i.e. DGRAD in the same or an earlier call.
+ *           needs da | db, i.e. DGRAD in the same or an earlier call.  With
+ *           FEPLB_BWD_ACCUMULATE added, WGRAD adds its results to what dw_gate, dw_up,
+ *           dw_down hold (gradient accumulation over micro-batches; an empty group's
+ *           matrices are then not touched) instead of overwriting them.
  *   ws      device, feplb_grouped_ffn_workspace_bytes(R_cap, g_end - g_begin) bytes
  * Rows past offsets[g_end] are neither read into any result nor written.
  * Limits: d % 256 == 0, f % 256 == 0, g_end <= FEPLB_MAX_GROUPS, R_cap >= 32 for WGRAD.
@@ -220,6 +223,7 @@ int32_t feplb_grouped_ffn(const void* Xp, const int32_t* row_src, int32_t T, int
 #define FEPLB_BWD_DGRAD 4
 #define FEPLB_BWD_WGRAD 8
 #define FEPLB_BWD_ALL 15
+#define FEPLB_BWD_ACCUMULATE 16
 
 int32_t feplb_grouped_ffn_train(const void* Xp, const int32_t* row_src, int32_t T, int32_t k,
                                 const int32_t* offsets,

@@ -7,7 +7,7 @@ from .binding import (  # noqa: F401
     feplb_grouped_ffn, feplb_grouped_ffn_workspace_bytes,
     feplb_unpermute_combine, feplb_stage_weights, feplb_stream_wait,
     feplb_expert_bytes, feplb_plan,
-    BWD_SCHEDULE, BWD_TRANSPOSE, BWD_DGRAD, BWD_WGRAD, BWD_ALL,
+    BWD_SCHEDULE, BWD_TRANSPOSE, BWD_DGRAD, BWD_WGRAD, BWD_ALL, BWD_ACCUMULATE,
     feplb_grouped_ffn_backward, feplb_grouped_ffn_backward_wt_bytes,
     feplb_combine_backward, feplb_route_topk_backward,
 )

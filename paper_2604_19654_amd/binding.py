@@ -20,6 +20,7 @@ MAX_GROUPS = 128   # FEPLB_MAX_GROUPS
 F32, BF16 = 0, 1
 FFN_GATE_UP, FFN_DOWN, FFN_SCHEDULE, FFN_ALL = 1, 2, 4, 7
 BWD_SCHEDULE, BWD_TRANSPOSE, BWD_DGRAD, BWD_WGRAD, BWD_ALL = 1, 2, 4, 8, 15
+BWD_ACCUMULATE = 16
 PLAN_WHOLE, PLAN_OVERFLOW = 0, 1
 
 

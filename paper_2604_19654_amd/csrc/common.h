@@ -14,7 +14,7 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 // backward-pass launchers (ffn_backward.hip), used by feplb_grouped_ffn_backward
 hipError_t launch_wgrad(const void* P, int ldp, int M, const void* Q, int ldq, int N, const int* offsets,
                         const int* order, int g_begin, int n_groups, int R_cap, void* const* c0, void* const* c1,
-                        int n_split, int ldc, hipStream_t s);
+                        int n_split, int ldc, bool accumulate, hipStream_t s);
 hipError_t launch_wgrad_order(const int* offsets, int g_begin, int n_groups, int R_cap, int* order, hipStream_t s);
 hipError_t launch_transpose(const void* const* src, int g_begin, int n_groups, int rows, int cols, void* dst,
                             size_t group_stride, hipStream_t s);

@@ -668,7 +668,7 @@ extern "C" int32_t feplb_grouped_ffn_backward(const void* Xp, const int32_t* off
                 "grouped_ffn_backward: negative size or empty range reversed");
   FEPLB_REQUIRE(g_end <= FEPLB_MAX_GROUPS, FEPLB_ESHAPE, "grouped_ffn_backward: g_end=%d above %d", g_end,
                 FEPLB_MAX_GROUPS);
-  FEPLB_REQUIRE((phases & ~FEPLB_BWD_ALL) == 0 && phases != 0, FEPLB_EINVAL,
+  FEPLB_REQUIRE((phases & ~(FEPLB_BWD_ALL | FEPLB_BWD_ACCUMULATE)) == 0 && (phases & FEPLB_BWD_ALL) != 0, FEPLB_EINVAL,
                 "grouped_ffn_backward: phases=%d", phases);
   FEPLB_REQUIRE(dxp_dtype == FEPLB_F32 || dxp_dtype == FEPLB_BF16, FEPLB_EINVAL,
                 "grouped_ffn_backward: unknown dxp_dtype %d", dxp_dtype);
@@ -744,11 +744,11 @@ extern "C" int32_t feplb_grouped_ffn_backward(const void* Xp, const int32_t* off
     guT.w0[g] = base + df;
   }
   if (do_w && R_cap > 0)   // dW_down = H^T dYp: before DGRAD, which does not touch H or dYp
-    FEPLB_HIP(feplb::launch_wgrad(H, f, f, dYp, d, d, offsets, order, g_begin, ng, R_cap, dw_down, nullptr, d, d, s));
+    FEPLB_HIP(feplb::launch_wgrad(H, f, f, dYp, d, d, offsets, order, g_begin, ng, R_cap, dw_down, nullptr, d, d, phases & FEPLB_BWD_ACCUMULATE, s));
   if (do_d && R_cap > 0)   // dH = dYp Wd^T, turned into [da | db] in place over the saved [a | b]
     FEPLB_HIP((launch_gemm<2, true>(dYp, d, nullptr, 0, 1, (const int4*)ws, d, f, f / 256, max_tiles, dT, nullptr, 0, s, AB, 2 * f)));
   if (do_w && R_cap > 0)   // [dW_gate | dW_up] = Xp^T [da | db]
-    FEPLB_HIP(feplb::launch_wgrad(Xp, d, d, AB, 2 * f, 2 * f, offsets, order, g_begin, ng, R_cap, dw_gate, dw_up, f, f, s));
+    FEPLB_HIP(feplb::launch_wgrad(Xp, d, d, AB, 2 * f, 2 * f, offsets, order, g_begin, ng, R_cap, dw_gate, dw_up, f, f, phases & FEPLB_BWD_ACCUMULATE, s));
   if (do_d && R_cap > 0) {   // dXp = [da | db] [Wg^T; Wu^T]
     if (dxp_dtype == FEPLB_BF16)
       FEPLB_HIP((launch_gemm<1, true>(AB, 2 * f, nullptr, 0, 1, (const int4*)ws, 2 * f, d, d / 256, max_tiles, guT, dXp, d, s)));

@@ -57,7 +57,7 @@ __global__ __launch_bounds__(FEPLB_MAX_GROUPS) void wgrad_order_kernel(const int
 __global__ __launch_bounds__(THREADS) void wgrad_gemm_kernel(
     const uint16_t* __restrict__ P, int ldp, const uint16_t* __restrict__ Q, int ldq,
     const int* __restrict__ offsets, const int* __restrict__ order, int g_begin, int n_groups, int R_cap,
-    int m_tiles, int n_tiles, int patch_n, int n_split, OutTable out, int ldc) {
+    int m_tiles, int n_tiles, int patch_n, int n_split, OutTable out, int ldc, int accumulate) {
   __shared__ __attribute__((aligned(1024))) char lds_p0[STAGE_BYTES];
   __shared__ __attribute__((aligned(1024))) char lds_p1[STAGE_BYTES];
   __shared__ __attribute__((aligned(1024))) char lds_p2[STAGE_BYTES];
@@ -96,6 +96,7 @@ __global__ __launch_bounds__(THREADS) void wgrad_gemm_kernel(
   const int lo = __builtin_amdgcn_readfirstlane(min(offsets[g], R_cap));
   const int hi = __builtin_amdgcn_readfirstlane(max(min(offsets[g + 1], R_cap), lo));
   const int KT = (hi - lo + BK - 1) / BK;
+  if (accumulate && KT == 0) return;   // nothing to add for an empty group
   // Row window of step kt: 32 rows from lo + 32 kt, except the last step, whose window ends at
   // the group's last row (moved back, never past the buffer) and is masked down to the rows the
   // earlier steps have not covered.
@@ -330,9 +331,11 @@ __global__ __launch_bounds__(THREADS) void wgrad_gemm_kernel(
 #pragma unroll
     for (int j = 0; j < 32 / RPI; ++j) {
       const int r = j * RPI + rd_row;
-      const uint4 v = *(const uint4*)(ep + r * ROW_BYTES + ((rd_chunk ^ (r & (CH - 1))) << 4));
-      const u32x4 vv = {v.x, v.y, v.z, v.w};
-      __builtin_nontemporal_store(vv, (u32x4*)(out_wave + (size_t)(mi * 32 + r) * ldc * 4 + rd_chunk * 16));
+      typedef float f32x4 __attribute__((ext_vector_type(4)));
+      f32x4 v = *(const f32x4*)(ep + r * ROW_BYTES + ((rd_chunk ^ (r & (CH - 1))) << 4));
+      f32x4* dst = (f32x4*)(out_wave + (size_t)(mi * 32 + r) * ldc * 4 + rd_chunk * 16);
+      if (accumulate) v += __builtin_nontemporal_load(dst);
+      __builtin_nontemporal_store(v, dst);
     }
   }
 }
@@ -379,9 +382,11 @@ namespace feplb {
 // C[g] = P_g^T Q_g for g in [g_begin, g_begin + n_groups): P [R_cap, ldp] columns [0, M),
 // Q [R_cap, ldq] columns [0, N); output fp32 row-major with row stride ldc; columns of the
 // product at or past n_split go to c1[g] (shifted by n_split).  M, N, n_split multiples of 256.
+// accumulate: the product is added to what the output matrices hold (an empty group's are left
+// alone) instead of replacing it.
 hipError_t launch_wgrad(const void* P, int ldp, int M, const void* Q, int ldq, int N, const int* offsets,
                         const int* order, int g_begin, int n_groups, int R_cap, void* const* c0, void* const* c1,
-                        int n_split, int ldc, hipStream_t s) {
+                        int n_split, int ldc, bool accumulate, hipStream_t s) {
   OutTable tab{};
   for (int i = 0; i < n_groups; ++i) {
     tab.c0[g_begin + i] = c0[g_begin + i];
@@ -395,7 +400,7 @@ hipError_t launch_wgrad(const void* P, int ldp, int M, const void* Q, int ldq, i
   const unsigned blocks = (unsigned)((patches + XCDS - 1) / XCDS) * XCDS * 32;
   hipLaunchKernelGGL(wgrad_gemm_kernel, dim3(blocks), dim3(THREADS), 0, s, (const uint16_t*)P, ldp,
                      (const uint16_t*)Q, ldq, offsets, order, g_begin, n_groups, R_cap, m_tiles, n_tiles, patch_n,
-                     n_split, tab, ldc);
+                     n_split, tab, ldc, accumulate ? 1 : 0);
   return hipGetLastError();
 }
 

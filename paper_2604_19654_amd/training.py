@@ -117,6 +117,6 @@ def time_phases(step: FfnTrainingStep, Xp, offsets, w_gate, w_up, w_down, dYp, r
     step.forward(Xp, offsets, w_gate, w_up, w_down)
     step.backward(Xp, offsets, w_gate, w_up, w_down, dYp)      # leaves tile table and transposes in place
     for name, ph in (("transpose", B.BWD_TRANSPOSE), ("dgrad", B.BWD_DGRAD), ("wgrad", B.BWD_WGRAD),
-                     ("backward", B.BWD_ALL)):
+                     ("wgrad_accumulating", B.BWD_WGRAD | B.BWD_ACCUMULATE), ("backward", B.BWD_ALL)):
         out[name] = timed(lambda ph=ph: step.backward(Xp, offsets, w_gate, w_up, w_down, dYp, phases=ph))
     return out

@@ -438,3 +438,52 @@ def test_grouped_ffn_backward_over_random_shapes():
             check_rows(f64(r["dXp"])[:r["R"]], dXp_o, f"case {case}: dXp")
         check_weight_grads(r, grads_o, f"case {case}")
         assert (r["dXp"][r["R"]:].float() == 512.0).all()
+
+
+def test_weight_gradients_accumulate_over_micro_batches():
+    # two micro-batches into the same fp32 gradient buffers: overwrite, then accumulate; the sum
+    # against the oracle's two gradients, and an empty group's buffers left as they were
+    d, f = 256, 256
+    batches = [[70, 0, 300], [33, 5, 0]]
+    G = 3
+    W = make_weights(G, d, f, 31)
+    Wd = [tuple(m.to(DEV) for m in w) for w in W]
+    wl = [[w[i] for w in Wd] for i in range(3)]
+    Wo = [tuple(f64(m) for m in w) for w in W]
+    dW = [[torch.full(s, 5.0, dtype=torch.float32, device=DEV) for _ in range(G)] for s in ((d, f), (d, f), (f, d))]
+    want = [[np.zeros(s) for s in ((d, f), (d, f), (f, d))] for _ in range(G)]
+    for bi, sizes in enumerate(batches):
+        off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+        R = int(off[-1])
+        gen = torch.Generator().manual_seed(40 + bi)
+        Xp = torch.randn((R, d), generator=gen).to(torch.bfloat16)
+        dYp = torch.randn((R, d), generator=gen).to(torch.bfloat16)
+        H = torch.zeros((R, f), dtype=torch.bfloat16, device=DEV)
+        AB = torch.zeros((R, 2 * f), dtype=torch.bfloat16, device=DEV)
+        Yp = torch.zeros((R, d), dtype=torch.float32, device=DEV)
+        dXp = torch.zeros((R, d), dtype=torch.float32, device=DEV)
+        off_dev = torch.from_numpy(off).to(DEV)
+        fe.feplb_grouped_ffn(Xp.to(DEV), off_dev, 0, G, d, f, *wl, H, Yp, AB=AB)
+        B.feplb_grouped_ffn_backward(Xp.to(DEV), off_dev, 0, G, d, f, *wl, H, AB, dYp.to(DEV), dXp, *dW,
+                                     phases=B.BWD_ALL | (B.BWD_ACCUMULATE if bi else 0))
+        torch.cuda.synchronize()
+        _, grads = orc.grouped_ffn_backward(f64(Xp), off, Wo, f64(dYp))
+        for g in range(G):
+            for i in range(3):
+                want[g][i] += grads[g][i]
+    for g in range(G):
+        for i in range(3):
+            check_rows(f64(dW[i][g]), want[g][i], f"accumulated gradient {i} of group {g}")
+    # group 1 was empty in the first batch (zeros written) and had 5 rows in the second
+    # a group that is empty in an accumulating call keeps its contents bit for bit
+    before = [m.clone() for m in (dW[0][2], dW[1][2], dW[2][2])]
+    off = torch.tensor([0, 40, 40, 40], dtype=torch.int32, device=DEV)
+    z = torch.randn((40, d), generator=torch.Generator().manual_seed(9)).to(torch.bfloat16).to(DEV)
+    H = torch.zeros((40, f), dtype=torch.bfloat16, device=DEV)
+    AB = torch.zeros((40, 2 * f), dtype=torch.bfloat16, device=DEV)
+    Yp = torch.zeros((40, d), dtype=torch.float32, device=DEV)
+    dXp = torch.zeros((40, d), dtype=torch.float32, device=DEV)
+    fe.feplb_grouped_ffn(z, off, 0, G, d, f, *wl, H, Yp, AB=AB)
+    B.feplb_grouped_ffn_backward(z, off, 0, G, d, f, *wl, H, AB, z, dXp, *dW, phases=B.BWD_ALL | B.BWD_ACCUMULATE)
+    torch.cuda.synchronize()
+    assert all(torch.equal(a, b) for a, b in zip(before, (dW[0][2], dW[1][2], dW[2][2])))
