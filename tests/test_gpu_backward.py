@@ -487,3 +487,32 @@ def test_weight_gradients_accumulate_over_micro_batches():
     B.feplb_grouped_ffn_backward(z, off, 0, G, d, f, *wl, H, AB, z, dXp, *dW, phases=B.BWD_ALL | B.BWD_ACCUMULATE)
     torch.cuda.synchronize()
     assert all(torch.equal(a, b) for a, b in zip(before, (dW[0][2], dW[1][2], dW[2][2])))
+
+
+def test_backward_capacity_below_the_row_count_truncates():
+    # offsets promise more rows than the buffers hold: every kernel stops at R_cap
+    d, f = 256, 256
+    sizes = [100, 60, 80]
+    R_cap = 130                      # group 1 is cut to 30 rows, group 2 to none
+    off_full = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    off_cut = np.minimum(off_full, R_cap).astype(np.int32)
+    gen = torch.Generator().manual_seed(77)
+    Xp = torch.randn((R_cap, d), generator=gen).to(torch.bfloat16)
+    dYp = torch.randn((R_cap, d), generator=gen).to(torch.bfloat16)
+    W = make_weights(3, d, f, 78)
+    Wd = [tuple(m.to(DEV) for m in w) for w in W]
+    wl = [[w[i] for w in Wd] for i in range(3)]
+    H = torch.zeros((R_cap, f), dtype=torch.bfloat16, device=DEV)
+    AB = torch.zeros((R_cap, 2 * f), dtype=torch.bfloat16, device=DEV)
+    Yp = torch.zeros((R_cap, d), dtype=torch.float32, device=DEV)
+    dXp = torch.zeros((R_cap, d), dtype=torch.float32, device=DEV)
+    dW = [[torch.full(s, 2.0, dtype=torch.float32, device=DEV) for _ in range(3)] for s in ((d, f), (d, f), (f, d))]
+    off_dev = torch.from_numpy(off_full).to(DEV)
+    fe.feplb_grouped_ffn(Xp.to(DEV), off_dev, 0, 3, d, f, *wl, H, Yp, AB=AB)
+    B.feplb_grouped_ffn_backward(Xp.to(DEV), off_dev, 0, 3, d, f, *wl, H, AB, dYp.to(DEV), dXp, *dW)
+    torch.cuda.synchronize()
+    Wo = [tuple(f64(m) for m in w) for w in W]
+    dXp_o, grads_o = orc.grouped_ffn_backward(f64(Xp), off_cut, Wo, f64(dYp))
+    check_rows(f64(dXp), dXp_o, "dXp")
+    r = dict(offsets=off_cut, dW=list(zip(*dW)))
+    check_weight_grads(r, grads_o, "truncated")
