@@ -136,12 +136,23 @@ extern "C" int32_t feplb_combine_backward(const void* dY, const void* Yp, int32_
   // Yp and dYp may be NULL only if no assignment is local; the kernel then never touches them.
   hipStream_t s = (hipStream_t)stream;
   const int blocks = (T + WAVES - 1) / WAVES;
-  if (yp_dtype == FEPLB_BF16)
-    hipLaunchKernelGGL((combine_backward_kernel<true, 4>), dim3(blocks), dim3(BLOCK), 0, s, (const u32x4*)dY, Yp,
-                       inv, topk_w, T, k, d, (u32x4*)dYp, dw);
-  else
-    hipLaunchKernelGGL((combine_backward_kernel<false, 4>), dim3(blocks), dim3(BLOCK), 0, s, (const u32x4*)dY, Yp,
-                       inv, topk_w, T, k, d, (u32x4*)dYp, dw);
+  // as many 16-byte pieces of the gradient row per lane as one pass over the row needs, up to 16
+  const int per_lane = (d / 8 + 63) / 64;
+#define FEPLB_COMBINE_BWD(BF, U)                                                                             \
+  hipLaunchKernelGGL((combine_backward_kernel<BF, U>), dim3(blocks), dim3(BLOCK), 0, s, (const u32x4*)dY, Yp, \
+                     inv, topk_w, T, k, d, (u32x4*)dYp, dw)
+  if (yp_dtype == FEPLB_BF16) {
+    if (per_lane <= 4) FEPLB_COMBINE_BWD(true, 4);
+    else if (per_lane <= 8) FEPLB_COMBINE_BWD(true, 8);
+    else if (per_lane <= 12) FEPLB_COMBINE_BWD(true, 12);
+    else FEPLB_COMBINE_BWD(true, 16);
+  } else {
+    if (per_lane <= 4) FEPLB_COMBINE_BWD(false, 4);
+    else if (per_lane <= 8) FEPLB_COMBINE_BWD(false, 8);
+    else if (per_lane <= 12) FEPLB_COMBINE_BWD(false, 12);
+    else FEPLB_COMBINE_BWD(false, 16);
+  }
+#undef FEPLB_COMBINE_BWD
   FEPLB_LAUNCH_CHECK("combine_backward_kernel");
   return FEPLB_OK;
 }
