@@ -149,7 +149,7 @@ def _permute_ms(p, steps):
 
 
 def training_leg(p, steps):
-    """Forward (keeping the gate/up products) and backward of the grouped FFN on the step's own
+    """Forward (keeping the SwiGLU derivatives) and backward of the grouped FFN on the step's own
     groups and token rows, with a synthetic upstream gradient; reported beside the forward step,
     not part of `value`."""
     import torch
@@ -180,11 +180,11 @@ def training_leg(p, steps):
                 combine_backward_gbps=(T * d * 2 + R * d * yp_bytes + R * d * 2 + T * k * 12) / (chain["combine_backward"] * 1e-3) / 1e9,
                 gather_backward_gbps=(R * d * st.dXp.element_size() + T * d * 2 + T * k * 8) / (chain["gather_backward"] * 1e-3) / 1e9,
                 flops_forward=3 * fl, flops_backward=6 * fl,
-                forward_tflops=3 * fl / (ms["forward_keeping_ab"] * 1e-3) / 1e12,
+                forward_tflops=3 * fl / (ms["forward_keeping_derivatives"] * 1e-3) / 1e12,
                 dgrad_tflops=3 * fl / (ms["dgrad"] * 1e-3) / 1e12,
                 wgrad_tflops=3 * fl / (ms["wgrad"] * 1e-3) / 1e12,
                 backward_tflops=6 * fl / (ms["backward"] * 1e-3) / 1e12,
-                backward_over_forward=ms["backward"] / ms["forward_keeping_ab"],
+                backward_over_forward=ms["backward"] / ms["forward_keeping_derivatives"],
                 note="backward = weight transposes + dH GEMM with the SwiGLU derivative + dXp GEMM + three ragged "
                      "weight-gradient GEMMs (fp32 out); upstream gradient synthetic; Xp materialised")
 
@@ -255,7 +255,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all", action="store_true", help="also time the other four workloads (reported under all_workloads)")
     ap.add_argument("--cpu-tokens", type=int, default=65536)
-    ap.add_argument("--no-training", action="store_true", help="skip the FFN training-step leg (forward keeping a|b, backward)")
+    ap.add_argument("--no-training", action="store_true", help="skip the FFN training-step leg (forward keeping the SwiGLU derivatives, backward)")
     ap.add_argument("--yp-dtype", default="f32", choices=["f32", "bf16"],
                     help="type of the expert outputs Yp between the down GEMM and the combine")
     ap.add_argument("--early-static", action="store_true",

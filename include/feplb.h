@@ -187,19 +187,21 @@ int32_t feplb_grouped_ffn(const void* Xp, const int32_t* row_src, int32_t T, int
  * ragged groups.  For every row r of group g, with a, b, H as above, s = sigmoid(a)
  * and the incoming gradient dYp[r,:]:
  *     dH = dYp[r,:] * W_down[g]^T
- *     da = dH * b * s * (1 + a (1 - s))      db = dH * a * s      (rounded to bf16)
+ *     da = dH * p,  p = b * s * (1 + a (1 - s))      db = dH * q,  q = a * s      (bf16)
  *     dXp[r,:] = da * W_gate[g]^T + db * W_up[g]^T
  *     dW_down[g] = sum_r H[r,:]^T dYp[r,:]   dW_gate[g] = sum_r Xp[r,:]^T da
  *     dW_up[g]   = sum_r Xp[r,:]^T db        (fp32, overwritten; zero for an empty group)
  *
  * feplb_grouped_ffn_train is feplb_grouped_ffn that also keeps what the backward
- * needs: AB, device bf16 [R_cap, 2f], receives a in columns [0,f) and b in [f,2f).
+ * needs: AB, device bf16 [R_cap, 2f], receives the two partial derivatives of the
+ * SwiGLU product, p = dH/da in columns [0,f) and q = dH/db in [f,2f), computed from
+ * the fp32 products a, b while they are in registers (one rounding each).
  *
  * feplb_grouped_ffn_backward:
  *   Xp      device, bf16 [R_cap,d], the permuted rows (a materialised copy; no row_src here)
  *   offsets, g_begin, g_end, R_cap, d, f, w_gate, w_up, w_down   as in the forward call
  *   H       device, bf16 [R_cap,f]   as written by the forward call
- *   AB      device, bf16 [R_cap,2f]  in: a | b from feplb_grouped_ffn_train; out: da | db
+ *   AB      device, bf16 [R_cap,2f]  in: p | q from feplb_grouped_ffn_train; out: da | db
  *   dYp     device, bf16 [R_cap,d]   gradient of the loss with respect to Yp
  *   dXp     device, [R_cap,d] of dxp_dtype (FEPLB_F32 or FEPLB_BF16)  out
  *   dw_gate, dw_up, dw_down  host arrays of (g_end) device pointers indexed by g:

@@ -253,8 +253,8 @@ def feplb_grouped_ffn(Xp, offsets, g_begin, g_end, d, f, w_gate, w_up, w_down, H
     tensors or raw device addresses.  H bf16 [R_cap,f]; Yp fp32 or bf16 [R_cap,d].
     With row_src (int32 [R_cap], from feplb_permute) and k, Xp is the unpermuted X [T,d] and the
     rows X[row_src[r] // k] are gathered as the gate/up GEMM loads them.
-    With AB (bf16 [R_cap,2f]) the call is feplb_grouped_ffn_train: the gate and up products are
-    kept in AB for feplb_grouped_ffn_backward."""
+    With AB (bf16 [R_cap,2f]) the call is feplb_grouped_ffn_train: the derivatives of the SwiGLU
+    product with respect to the gate and up products are kept in AB for feplb_grouped_ffn_backward."""
     R_cap = H.shape[0]
     yp_dtype = F32
     if Yp is not None:

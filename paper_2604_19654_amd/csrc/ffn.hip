@@ -7,9 +7,11 @@
 //             the token row X[row_src[r] / k, :] gathered while it is loaded
 //   down    : Yp[r,:] = H[r,:] Wd[g]
 // The same kernel serves training (Section 3.2 times the backward pass as well): the gate_up
-// form can also keep the two products a = x Wg, b = x Wu (bf16) for the backward pass, and two
-// more forms give the input gradients,
-//   dswiglu : dH = dYp Wd^T, then [da | db] = dH * d(silu(a) b)/d(a, b), written over [a | b]
+// form can also keep, for the backward pass, the two partial derivatives of its output with
+// respect to the products a = x Wg and b = x Wu,
+//   p = dH/da = b s (1 + a (1 - s)),   q = dH/db = a s,   s = sigmoid(a)        (bf16),
+// and two more forms give the input gradients,
+//   dswiglu : dH = dYp Wd^T, then [da | db] = [dH p | dH q], written over [p | q]
 //   plain   : dXp = [da | db] [Wg^T; Wu^T]   (the down form with another K)
 // with the transposed weights made by a small kernel of ffn_backward.hip, which also holds the
 // ragged weight-gradient GEMM.
@@ -98,12 +100,13 @@ __global__ __launch_bounds__(SCHED_THREADS) void ffn_schedule_kernel(
   if (i == 0) ws[0] = make_int4(total, 0, 0, 0);
 }
 
-// MODE 0: gate_up (+SwiGLU, bf16 out; with SAVE the gate and up products are also stored, as bf16,
-//         in columns [0,N) and [N,2N) of `aux`, for the backward pass);
+// MODE 0: gate_up (+SwiGLU, bf16 out; with SAVE the derivatives p, q of the SwiGLU product with
+//         respect to the gate and up products are also stored, as bf16, in columns [0,N) and
+//         [N,2N) of `aux`, for the backward pass);
 // MODE 1: plain GEMM (down, or the input gradient), fp32 or bf16 out;
-// MODE 2: backward of the SwiGLU product: the GEMM result is dH; `aux` holds the saved gate | up
-//         products a | b on entry and their gradients on exit,
-//         da = dH b s (1 + a (1 - s)),  db = dH a s,  s = sigmoid(a); `out` is not used.
+// MODE 2: backward of the SwiGLU product: the GEMM result is dH; `aux` holds the saved
+//         derivatives p | q on entry and the gradients da = dH p | db = dH q on exit; `out` is
+//         not used.
 template <int MODE, bool OUT_BF16, bool SAVE>
 __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
     const uint16_t* __restrict__ A, int lda, const int* __restrict__ row_src, int n_src_rows, int src_k,
@@ -435,7 +438,7 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
     }
   };
   if constexpr (MODE == 2) {
-    // a | b come in as whole lines, pass through the staging region (a in its first 8 KB, b in
+    // p | q come in as whole lines, pass through the staging region (p in its first 8 KB, q in
     // the second) to reach the lanes that hold the matching dH values, and leave the same way
     char* aux_wave = (char*)aux + ((size_t)(row0 + wm * 128) * ld_aux + col0) * 2;
     const size_t b_shift = (size_t)N * 2;                        // b sits N columns to the right of a
@@ -464,16 +467,15 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
           char* q = piece(nj, c);
-          const uint2 av = *(const uint2*)q, bv = *(const uint2*)(q + 8192);
-          const float a[4] = {bf16_lo(av.x), bf16_hi(av.x), bf16_lo(av.y), bf16_hi(av.y)};
-          const float b[4] = {bf16_lo(bv.x), bf16_hi(bv.x), bf16_lo(bv.y), bf16_hi(bv.y)};
+          const uint2 pv = *(const uint2*)q, qv = *(const uint2*)(q + 8192);
+          const float dp[4] = {bf16_lo(pv.x), bf16_hi(pv.x), bf16_lo(pv.y), bf16_hi(pv.y)};
+          const float dq[4] = {bf16_lo(qv.x), bf16_hi(qv.x), bf16_lo(qv.y), bf16_hi(qv.y)};
           float da[4], db[4];
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const float dh = acc[mi][nj][4 * c + i];
-            const float sg = __builtin_amdgcn_rcpf(1.0f + __expf(-a[i]));
-            db[i] = dh * a[i] * sg;
-            da[i] = dh * b[i] * sg * (1.0f + a[i] * (1.0f - sg));
+            da[i] = dh * dp[i];
+            db[i] = dh * dq[i];
           }
           *(uint2*)q = make_uint2(pack_bf16(da[0], da[1]), pack_bf16(da[2], da[3]));
           *(uint2*)(q + 8192) = make_uint2(pack_bf16(db[0], db[1]), pack_bf16(db[2], db[3]));
@@ -487,8 +489,35 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
     char* out_wave = (char*)out + ((size_t)(row0 + wm * 128) * ldo + col0) * ESZ;
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi) {
+      if constexpr (MODE == 0 && SAVE) {
+        // H and the two derivatives share the sigmoid; the three 4 KB pieces of the pass sit
+        // behind each other in the staging region
 #pragma unroll
-      for (int what = 0; what < (MODE == 0 && SAVE ? 3 : 1); ++what) {
+        for (int nj = 0; nj < 2; ++nj)
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            char* dst = piece(nj, c);
+            float hv[4], pv[4], qv[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const float a = acc[mi][nj][4 * c + i], b = acc[mi][nj + 2][4 * c + i];
+              const float sg = __builtin_amdgcn_rcpf(1.0f + __expf(-a));
+              qv[i] = a * sg;                              // silu(a) = dH/db
+              hv[i] = qv[i] * b;
+              pv[i] = b * sg * (1.0f + a - qv[i]);         // dH/da; a (1 - s) = a - a s
+            }
+            *(uint2*)dst = make_uint2(pack_bf16(hv[0], hv[1]), pack_bf16(hv[2], hv[3]));
+            *(uint2*)(dst + 4096) = make_uint2(pack_bf16(pv[0], pv[1]), pack_bf16(pv[2], pv[3]));
+            *(uint2*)(dst + 8192) = make_uint2(pack_bf16(qv[0], qv[1]), pack_bf16(qv[2], qv[3]));
+          }
+        char* aux_wave = (char*)aux + ((size_t)(row0 + wm * 128) * ld_aux + col0) * 2;
+        store_lines(mi, out_wave, ldo * ESZ, false);
+        ep += 4096;
+        store_lines(mi, aux_wave, ld_aux * 2, false);
+        ep += 4096;
+        store_lines(mi, aux_wave + (size_t)N * 2, ld_aux * 2, false);
+        ep -= 8192;
+      } else {
 #pragma unroll
         for (int nj = 0; nj < (MODE == 0 ? 2 : 4); ++nj)
 #pragma unroll
@@ -496,23 +525,14 @@ __global__ __launch_bounds__(THREADS) void grouped_gemm_kernel(
             char* dst = piece(nj, c);
             float v[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              if (MODE == 0)
-                v[i] = what == 0 ? silu(acc[mi][nj][4 * c + i]) * acc[mi][nj + 2][4 * c + i]
-                                 : acc[mi][what == 1 ? nj : nj + 2][4 * c + i];
-              else
-                v[i] = acc[mi][nj][4 * c + i];
-            }
+            for (int i = 0; i < 4; ++i)
+              v[i] = MODE == 0 ? silu(acc[mi][nj][4 * c + i]) * acc[mi][nj + 2][4 * c + i] : acc[mi][nj][4 * c + i];
             if (ESZ == 2)
               *(uint2*)dst = make_uint2(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]));
             else
               *(float4*)dst = make_float4(v[0], v[1], v[2], v[3]);
           }
-        if (what == 0)
-          store_lines(mi, out_wave, ldo * ESZ, MODE == 1 && !OUT_BF16);
-        else   // saved gate (what 1) and up (what 2) products
-          store_lines(mi, (char*)aux + ((size_t)(row0 + wm * 128) * ld_aux + (what - 1) * N + col0) * 2,
-                      ld_aux * 2, false);
+        store_lines(mi, out_wave, ldo * ESZ, MODE == 1 && !OUT_BF16);
       }
     }
   }

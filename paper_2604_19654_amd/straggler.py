@@ -79,7 +79,7 @@ class FfnTimer:
         self.e0, self.e1 = B.HipEvent(), B.HipEvent()
 
     def time_train_ms(self, sizes: Sequence[int], reps: int = 2):
-        """(forward keeping the gate/up products, backward) of one share, in ms."""
+        """(forward keeping the SwiGLU derivatives, backward) of one share, in ms."""
         from .training import FfnTrainingStep
         G = len(sizes)
         if G == 0 or sum(sizes) == 0:
@@ -182,7 +182,7 @@ def main():
     ap.add_argument("--tau", type=int, default=0)
     ap.add_argument("--no-gemm", action="store_true")
     ap.add_argument("--backward", action="store_true",
-                    help="also time every rank's FFN training step (forward keeping a|b, backward) and report the slowest rank's times before and after the plan")
+                    help="also time every rank's FFN training step (forward keeping the SwiGLU derivatives, backward) and report the slowest rank's times before and after the plan")
     a = ap.parse_args()
     B.lib()
     rows = []

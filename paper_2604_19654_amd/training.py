@@ -1,5 +1,5 @@
 """Buffers and call sequence of one training step of the grouped expert FFN (forward that keeps
-the gate/up products, then the backward pass; paper Section 3.2 reports both times).  Only
+the SwiGLU derivatives, then the backward pass; paper Section 3.2 reports both times).  Only
 allocation and sequencing live here: every step is a library call."""
 from __future__ import annotations
 
@@ -12,7 +12,8 @@ from . import binding as B
 
 class FfnTrainingStep:
     """Holds what feplb_grouped_ffn (training form) and feplb_grouped_ffn_backward need for G
-    groups and up to R_cap permuted rows: H, a|b (turned into da|db by the backward), Yp, dXp,
+    groups and up to R_cap permuted rows: H, the SwiGLU derivatives p|q (turned into da|db by the
+    backward), Yp, dXp,
     the fp32 weight gradients, the transposed-weight scratch and the workspace."""
 
     def __init__(self, R_cap: int, G: int, d: int, f: int, device="cuda:0", dxp_dtype=torch.float32):
@@ -113,7 +114,7 @@ def time_phases(step: FfnTrainingStep, Xp, offsets, w_gate, w_up, w_down, dYp, r
         e1.synchronize()
         return e0.elapsed_ms(e1) / reps
 
-    out = {"forward_keeping_ab": timed(lambda: step.forward(Xp, offsets, w_gate, w_up, w_down))}
+    out = {"forward_keeping_derivatives": timed(lambda: step.forward(Xp, offsets, w_gate, w_up, w_down))}
     step.forward(Xp, offsets, w_gate, w_up, w_down)
     step.backward(Xp, offsets, w_gate, w_up, w_down, dYp)      # leaves tile table and transposes in place
     for name, ph in (("transpose", B.BWD_TRANSPOSE), ("dgrad", B.BWD_DGRAD), ("wgrad", B.BWD_WGRAD),

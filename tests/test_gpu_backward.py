@@ -2,7 +2,7 @@
 C ABI.  The oracle differentiates the float64 definition; the library keeps its activations and
 their gradients in bf16, so every output row is held to BWD_RMS_TOL (root-mean-square error) and
 BWD_MAX_TOL (largest error) of that row's RMS; tests/util.py derives both bars.  Beside each result the tests print what a float64
-computation that merely stores a, b, H, da, db in bf16 would get: a diagnostic, not a bound.
+computation that merely stores p, q, H, da, db in bf16 would get: a diagnostic, not a bound.
 Needs an MI355X: run with -m gpu."""
 import numpy as np
 import pytest
@@ -69,7 +69,7 @@ def bf16_round(x):
 
 
 def storage_format_floor(r, dXp_o, grads_o, Wo):
-    """Worst row error of a float64 backward whose only inexactness is keeping a, b, H, da, db in
+    """Worst row error of a float64 backward whose only inexactness is keeping p, q, H, da, db in
     bf16 (diagnostic printed beside the library's figures)."""
     R = r["R"]
     X, dY = f64(r["Xp"])[:R], f64(r["dYp"])[:R]
@@ -81,10 +81,10 @@ def storage_format_floor(r, dXp_o, grads_o, Wo):
         x, dy = X[lo:hi], dY[lo:hi]
         a0, b0 = x @ wg, x @ wu
         h = bf16_round(a0 / (1.0 + np.exp(-a0)) * b0)
-        a, b = bf16_round(a0), bf16_round(b0)
-        sg = 1.0 / (1.0 + np.exp(-a))
+        sg = 1.0 / (1.0 + np.exp(-a0))
+        dp, dq = bf16_round(b0 * sg * (1.0 + a0 * (1.0 - sg))), bf16_round(a0 * sg)
         dh = dy @ wd.T
-        da, db = bf16_round(dh * b * sg * (1.0 + a * (1.0 - sg))), bf16_round(dh * a * sg)
+        da, db = bf16_round(dh * dp), bf16_round(dh * dq)
         dx = da @ wg.T + db @ wu.T
         worst[0] = max(worst[0], row_rms_err(dx, dXp_o[lo:hi]).max())
         worst[1] = max(worst[1], row_rel_err(dx, dXp_o[lo:hi]).max())
@@ -127,17 +127,20 @@ def test_grouped_ffn_backward_parity(sizes, d, f, dxp_dtype):
     R = r["R"]
     (dXp_o, grads_o), Wo = oracle_backward(r)
     if R:
-        # what the forward kept: a | b within a bf16 rounding step of the float64 products
+        # what the forward kept: the derivatives p = dH/da, q = dH/db of the SwiGLU product,
+        # within a bf16 rounding step of their float64 values
         X64 = f64(r["Xp"])[:R]
-        a_o = np.zeros((R, f)); b_o = np.zeros((R, f))
+        p_o = np.zeros((R, f)); q_o = np.zeros((R, f))
         for g in range(len(sizes)):
             lo, hi = int(r["offsets"][g]), int(r["offsets"][g + 1])
-            a_o[lo:hi] = X64[lo:hi] @ Wo[g][0]
-            b_o[lo:hi] = X64[lo:hi] @ Wo[g][1]
-        ea = bf16_rounding_excess(f64(r["AB_saved"])[:R, :f], a_o)
-        eb = bf16_rounding_excess(f64(r["AB_saved"])[:R, f:], b_o)
+            a_g, b_g = X64[lo:hi] @ Wo[g][0], X64[lo:hi] @ Wo[g][1]
+            s_g = 1.0 / (1.0 + np.exp(-a_g))
+            p_o[lo:hi] = b_g * s_g * (1.0 + a_g * (1.0 - s_g))
+            q_o[lo:hi] = a_g * s_g
+        ea = bf16_rounding_excess(f64(r["AB_saved"])[:R, :f], p_o)
+        eb = bf16_rounding_excess(f64(r["AB_saved"])[:R, f:], q_o)
         ex = check_rows(f64(r["dXp"])[:R], dXp_o, "dXp")
-        say(f"  saved a, b rounding excess {ea:.3f} {eb:.3f} (<= 1)  dXp rms {ex[0]:.5f} max {ex[1]:.5f}")
+        say(f"  saved p, q rounding excess {ea:.3f} {eb:.3f} (<= 1)  dXp rms {ex[0]:.5f} max {ex[1]:.5f}")
         assert ea <= 1.0 and eb <= 1.0
     worst = check_weight_grads(r, grads_o, "parity")
     say(f"  weight gradients rms {worst[0]:.5f} max {worst[1]:.5f} (<= {BWD_RMS_TOL}, {BWD_MAX_TOL})")

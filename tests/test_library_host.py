@@ -67,7 +67,7 @@ def test_argument_validation_happens_before_any_device_work():
               None, 0, 15, None, 0, None) == 0                                           # empty range: nothing to do
     assert fe.binding.feplb_grouped_ffn_backward_wt_bytes(20, 6144, 2048) == 20 * 72 * 2**20   # one transposed copy of every expert
     assert L.feplb_grouped_ffn_train(None, None, 0, 0, None, 0, 1, 128, 256, 128, None, None, None, None, None, None,
-                                     0, 7, None, 0, None) == -1                          # keeping a | b needs the AB buffer
+                                     0, 7, None, 0, None) == -1                          # keeping the derivatives needs the AB buffer
     assert L.feplb_combine_backward(None, None, 0, None, None, 4, 2, 12, None, None, None) == -2     # d % 8
     assert L.feplb_combine_backward(None, None, 9, None, None, 4, 2, 16, None, None, None) == -1     # dtype
     assert L.feplb_combine_backward(None, None, 0, None, None, 0, 2, 16, None, None, None) == 0      # no tokens
