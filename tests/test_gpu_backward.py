@@ -519,3 +519,25 @@ def test_backward_capacity_below_the_row_count_truncates():
     check_rows(f64(dXp), dXp_o, "dXp")
     r = dict(offsets=off_cut, dW=list(zip(*dW)))
     check_weight_grads(r, grads_o, "truncated")
+
+
+def test_training_step_with_the_largest_group_count():
+    # 128 groups (the limit of the by-value pointer tables), most of them tiny or empty
+    rng = np.random.default_rng(128)
+    sizes = [int(v) for v in rng.choice([0, 0, 1, 3, 17, 40, 70], size=B.MAX_GROUPS)]
+    sizes[5], sizes[77], sizes[127] = 300, 260, 33
+    d, f = 256, 256
+    say(f"ffn backward with {len(sizes)} groups, {sum(sizes)} rows")
+    r = run_forward_backward(sizes, d, f, torch.float32, seed=128)
+    (dXp_o, grads_o), _ = oracle_backward(r)
+    check_rows(f64(r["dXp"])[:r["R"]], dXp_o, "dXp")
+    check_weight_grads(r, grads_o, "128 groups")
+    # the forward's outputs on the same call: Yp against the oracle
+    _, Yp_o = orc.grouped_ffn(f64(r["Xp"])[:r["R"]], r["offsets"], [tuple(f64(m) for m in w) for w in r["W"]])
+    assert row_rel_err(f64(r["Yp"])[:r["R"]], Yp_o).max() <= 2e-2
+    with pytest.raises(B.FeplbError):       # one group more than the tables hold
+        off = torch.zeros((B.MAX_GROUPS + 2,), dtype=torch.int32, device=DEV)
+        z = torch.zeros((64, d), dtype=torch.bfloat16, device=DEV)
+        w = [torch.zeros((d, f), dtype=torch.bfloat16, device=DEV)] * (B.MAX_GROUPS + 1)
+        fe.feplb_grouped_ffn(z, off, 0, B.MAX_GROUPS + 1, d, f, w, w, w, torch.zeros((64, f), dtype=torch.bfloat16, device=DEV),
+                             torch.zeros((64, d), dtype=torch.float32, device=DEV))
