@@ -270,6 +270,16 @@ def test_backward_at_full_size_on_sampled_outputs(name):
         say(f"  group {g} ({hi - lo} rows) checked")
     for g in np.nonzero(sizes == 0)[0][:3]:
         assert not st.dW_gate[g].any() and not st.dW_up[g].any() and not st.dW_down[g].any()
+    # the same step again, several times: every output bit for bit (counted waits of the
+    # pipelines leave no room for a load that lands late)
+    big = int(order[0])
+    ref = (st.dXp.clone(), st.AB.clone(), st.dW_gate[big].clone(), st.dW_down[big].clone())
+    for _ in range(4):
+        st.forward(Xp, offsets, wg, wu, wd)
+        st.backward(Xp, offsets, wg, wu, wd, dYp)
+        torch.cuda.synchronize()
+        now = (st.dXp, st.AB, st.dW_gate[big], st.dW_down[big])
+        assert all(torch.equal(a_, b_) for a_, b_ in zip(ref, now)), "training step is not repeatable"
     say(f"  dXp rms {worst[0]:.5f} max {worst[1]:.5f}; weight gradients rms {worst[2]:.5f} max {worst[3]:.5f}")
     p.wl.drop_weights()
     torch.cuda.empty_cache()
