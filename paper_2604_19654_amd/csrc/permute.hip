@@ -219,7 +219,7 @@ __global__ __launch_bounds__(BLOCK) void gather_rows_kernel(const u32x4* __restr
     for (int u = 0; u < UNROLL; ++u) {
       const int v = v0 + u * 64 + lane;
       if (v < nvec) {
-        dst[v] = p[u];
+        __builtin_nontemporal_store(p[u], dst + v);   // written once, read by a later kernel
       }
     }
   }
