@@ -23,6 +23,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 (no sparsity)
+HBM_PEAK_GBPS = 8000.0           # MI355X HBM3E
 HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch of the gate/up GEMM (read + written), measured with rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE and calibrated against the row-copy kernel of the same run; see
@@ -114,6 +115,17 @@ def time_workload(name, steps, warmup, source_kind="device", fused_gather=True, 
     # the permute step with its row gather (X -> Xp), timed on its own when the step's GEMM gathers the rows itself
     res["permute_with_gather_ms"] = ms["permute"] if ("permute" in ms and not fused_gather) else _permute_ms(p, steps)
     res["permute_gbps"] = (2 * R * d * 2 + T * k * 8 + R * 4) / (res["permute_with_gather_ms"] * 1e-3) / 1e9
+    # the row copy alone: the step with the gather minus the index kernels timed without it
+    res["permute_indices_ms"] = _permute_ms(p, steps, with_rows=False)
+    gather_ms = max(res["permute_with_gather_ms"] - res["permute_indices_ms"], 1e-6)
+    res["hbm_kernels"] = {
+        "peak_gbps": HBM_PEAK_GBPS,
+        "combine": {"ms": ms["combine"], "gbps": res["combine_gbps"], "frac": res["combine_gbps"] / HBM_PEAK_GBPS},
+        "permute_with_gather": {"ms": res["permute_with_gather_ms"], "gbps": res["permute_gbps"],
+                                "frac": res["permute_gbps"] / HBM_PEAK_GBPS},
+        "row_gather_alone": {"ms": gather_ms, "gbps": 2 * R * d * 2 / (gather_ms * 1e-3) / 1e9,
+                             "frac": 2 * R * d * 2 / (gather_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS},
+    }
     if p.rebalanced:
         nbytes = sum(t.numel() * t.element_size() for t in p.remote_sources.values())
         if early_static:
@@ -130,14 +142,16 @@ def time_workload(name, steps, warmup, source_kind="device", fused_gather=True, 
     return p, res
 
 
-def _permute_ms(p, steps):
-    """feplb_permute including the row gather into a permuted copy, on the step's own routing."""
+def _permute_ms(p, steps, with_rows=True):
+    """feplb_permute on the step's own routing: with the row gather into a permuted copy, or the
+    index part alone."""
     import torch
     from paper_2604_19654_amd import binding as B
     lay, b = p.layer, p.layer.buf
     G = len(p.groups)
-    Xp = torch.empty((lay.R_cap, lay.d), dtype=torch.bfloat16, device=p.wl.X.device)
-    args = (b.topk_ids, lay.E, p.groups, p.wl.X, lay.R_cap, Xp, b.offsets[: G + 1], b.row_src, b.inv, b.ws_permute)
+    Xp = torch.empty((lay.R_cap, lay.d), dtype=torch.bfloat16, device=p.wl.X.device) if with_rows else None
+    args = (b.topk_ids, lay.E, p.groups, p.wl.X if with_rows else None, lay.R_cap, Xp, b.offsets[: G + 1], b.row_src,
+            b.inv, b.ws_permute)
     e0, e1 = B.HipEvent(), B.HipEvent()
     B.feplb_permute(*args)
     e0.record(None)
