@@ -354,7 +354,7 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(WeightTable src, in
   for (int i = 0; i < 2; ++i) {
     const int idx = t + i * 256;           // 512 pieces of 8 elements
     const int r = idx / 8, c8 = (idx % 8) * 8;
-    const uint4 v = *(const uint4*)(W + (size_t)(r0 + r) * cols + c0 + c8);
+    const u32x4 v = __builtin_nontemporal_load((const u32x4*)(W + (size_t)(r0 + r) * cols + c0 + c8));
     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -371,7 +371,8 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(WeightTable src, in
 #pragma unroll
     for (int e = 0; e < 4; ++e)
       w[e] = (uint32_t)tile[r8 + 2 * e][c] | ((uint32_t)tile[r8 + 2 * e + 1][c] << 16);
-    *(uint4*)(WT + (size_t)(c0 + c) * rows + r0 + r8) = make_uint4(w[0], w[1], w[2], w[3]);
+    const u32x4 o = {w[0], w[1], w[2], w[3]};
+    __builtin_nontemporal_store(o, (u32x4*)(WT + (size_t)(c0 + c) * rows + r0 + r8));
   }
 }
 
