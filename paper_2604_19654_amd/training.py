@@ -30,14 +30,23 @@ class FfnTrainingStep:
         self.WT = torch.empty((max(B.feplb_grouped_ffn_backward_wt_bytes(G, d, f), 16),), dtype=torch.uint8, device=dev)
         self.ws = torch.empty((B.feplb_grouped_ffn_workspace_bytes(R, G),), dtype=torch.uint8, device=dev)
 
+    def _need_rows(self, t, name):
+        # the kernels size their grids by R_cap and the weight gradients read whole 32-row windows
+        if t.shape[0] < self.R_cap or t.shape[1] != self.d:
+            raise B.FeplbError(f"{name} must be [{self.R_cap}, {self.d}] (rows past the last group are not used), "
+                               f"got {tuple(t.shape)}")
+
     def forward(self, Xp, offsets, w_gate, w_up, w_down, stream=None):
         """Xp bf16 [R_cap,d] (a materialised permuted copy, which the backward reads again)."""
+        self._need_rows(Xp, "Xp")
         B.feplb_grouped_ffn(Xp, offsets, 0, self.G, self.d, self.f, w_gate, w_up, w_down, self.H, self.Yp,
                             ws=self.ws, stream=stream, AB=self.AB)
         return self.Yp
 
     def backward(self, Xp, offsets, w_gate, w_up, w_down, dYp, phases=B.BWD_ALL, stream=None):
         """dYp bf16 [R_cap,d] -> dXp; the weight gradients land in dW_gate / dW_up / dW_down."""
+        self._need_rows(Xp, "Xp")
+        self._need_rows(dYp, "dYp")
         B.feplb_grouped_ffn_backward(Xp, offsets, 0, self.G, self.d, self.f, w_gate, w_up, w_down, self.H, self.AB,
                                      dYp, self.dXp, self.dW_gate, self.dW_up, self.dW_down, WT=self.WT,
                                      phases=phases, ws=self.ws, stream=stream)
