@@ -49,6 +49,7 @@ def time_workload(name, steps, warmup, source_kind="device", fused_gather=True, 
     torch.cuda.synchronize()
     tl = layer.timeline
     acc = {}
+    per_step = []
     t0 = time.perf_counter()
     for _ in range(steps):
         runner.step(p, mark=True, early_static=early_static)
@@ -61,6 +62,7 @@ def time_workload(name, steps, warmup, source_kind="device", fused_gather=True, 
                 acc[key] = acc.get(key, 0.0) + tl[a].elapsed_ms(tl[b])
         span("start", "routed", "route")
         span("start", "combined", "step_events")
+        per_step.append(tl["start"].elapsed_ms(tl["combined"]))
         if p.rebalanced:
             span("static_scheduled", "static_gate_up", "gate_up")
             span("static_gate_up", "static_down", "down")
@@ -87,6 +89,7 @@ def time_workload(name, steps, warmup, source_kind="device", fused_gather=True, 
     res = dict(
         workload=name, T=T, R=R, d=d, f=f, E=wl.E, k=k, groups=len(p.groups), rank=p.rank,
         ms_per_step=wall_ms, ms=ms,
+        step_events_ms_median=float(np.median(per_step)), step_events_ms_min=float(np.min(per_step)),
         ffn_tflops_step=ffn_flops / (wall_ms * 1e-3) / 1e12,
         ffn_tflops_kernels=ffn_flops / ((ms["gate_up"] + ms["down"]) * 1e-3) / 1e12,
         gate_up_tflops=4.0 * d * f * R / (ms["gate_up"] * 1e-3) / 1e12,
