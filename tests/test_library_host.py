@@ -136,3 +136,47 @@ def test_plan_error_codes():
         fe.feplb_plan(2, [0, 0, 1], [9, 5, 0], [1, 1, 1], [4, 4], 1, fe.PLAN_WHOLE, -1, max_moves=0)
     with pytest.raises(fe.FeplbError):
         fe.feplb_plan(2, [0, 1], [1, 1], [1, 1], [1, 1], 0, 9)      # unknown mode
+
+
+def test_header_is_plain_c_and_the_library_links_from_c(tmp_path):
+    """The boundary is a C ABI: a C99 translation unit that includes the header compiles with gcc,
+    links against the library and runs its host-only entry points (no GPU is touched)."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "use_feplb.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include <string.h>
+#include "feplb.h"
+int main(void) {
+  /* two ranks, four experts, one free slot each, rank 0 overloaded */
+  int32_t owner[4] = {0, 0, 1, 1}, slots[2] = {1, 1}, n_moves = -1, chosen = -7;
+  int64_t n[4] = {50, 30, 5, 5}, before[2], after[2];
+  uint8_t dyn[4] = {1, 1, 1, 1};
+  feplb_move moves[4];
+  int32_t rc = feplb_plan(2, 4, owner, n, dyn, slots, 0, FEPLB_PLAN_WHOLE, -1, moves, 4, &n_moves, before, after, &chosen);
+  if (rc != FEPLB_OK) { printf("plan failed: %s\n", feplb_last_error()); return 1; }
+  printf("%s moves=%d expert=%d %d->%d rows=%lld before=%lld,%lld after=%lld,%lld bytes=%zu\n", feplb_version(), n_moves,
+         moves[0].expert, moves[0].src, moves[0].dst, (long long)moves[0].rows, (long long)before[0],
+         (long long)before[1], (long long)after[0], (long long)after[1], feplb_expert_bytes(6144, 2048, 2));
+  /* a refused call launches nothing and leaves a message */
+  rc = feplb_route_topk(NULL, 4, 4, 5, NULL, NULL, NULL, NULL);
+  return (rc == FEPLB_ESHAPE && strstr(feplb_last_error(), "route_topk")) ? 0 : 2;
+}
+''')
+    exe = tmp_path / "use_feplb"
+    libdir = os.path.dirname(fe.lib_path())
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"), str(src),
+                    "-o", str(exe), "-L", libdir, "-lfeplb", f"-Wl,-rpath,{libdir}", "-Wl,-rpath,/opt/rocm/lib"],
+                   check=True, capture_output=True, text=True)
+    r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=60)
+    assert r.returncode == 0, r.stdout + r.stderr
+    m_o, b_o, a_o = orc.plan_whole(2, [0, 0, 1, 1], [50, 30, 5, 5], [1, 1, 1, 1], [1, 1], 0)
+    e0, s0, d0, rows0 = (int(v) for v in m_o[0][:4])
+    want = (f"moves={len(m_o)} expert={e0} {s0}->{d0} rows={rows0} before={b_o[0]},{b_o[1]} "
+            f"after={a_o[0]},{a_o[1]}")
+    assert want in r.stdout, (want, r.stdout)
+    assert want == "moves=2 expert=0 0->1 rows=50 before=80,10 after=35,55"     # worked by hand from Section 2.3's rule
+    assert f"bytes={72 * 2**20}" in r.stdout
