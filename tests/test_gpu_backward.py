@@ -551,3 +551,36 @@ def test_training_step_with_the_largest_group_count():
         w = [torch.zeros((d, f), dtype=torch.bfloat16, device=DEV)] * (B.MAX_GROUPS + 1)
         fe.feplb_grouped_ffn(z, off, 0, B.MAX_GROUPS + 1, d, f, w, w, w, torch.zeros((64, f), dtype=torch.bfloat16, device=DEV),
                              torch.zeros((64, d), dtype=torch.float32, device=DEV))
+
+
+def test_training_forward_gathering_rows_equals_reading_the_permuted_copy():
+    # feplb_grouped_ffn_train with row_src (rows gathered from X as they are loaded) against the
+    # same call on a materialised Xp: H, the kept derivatives and Yp bit for bit
+    T, E, k, d, f = 700, 8, 2, 512, 256
+    rng = np.random.default_rng(5)
+    ids = np.stack([rng.permutation(E)[:k] for _ in range(T)]).astype(np.int32)
+    groups = [(e, 0, B.ORD_MAX) for e in (0, 3, 5, 6)]
+    G = len(groups)
+    X = torch.randn((T, d), generator=torch.Generator().manual_seed(6)).to(torch.bfloat16).to(DEV)
+    R_cap = T * k
+    Xp, offsets, row_src, inv = B.feplb_permute(torch.from_numpy(ids).to(DEV), E, groups, X, R_cap)
+    W = [tuple(m.to(DEV) for m in w) for w in make_weights(G, d, f, 9)]
+    wl = [[w[i] for w in W] for i in range(3)]
+    outs = []
+    for gather in (False, True):
+        H = torch.zeros((R_cap, f), dtype=torch.bfloat16, device=DEV)
+        AB = torch.zeros((R_cap, 2 * f), dtype=torch.bfloat16, device=DEV)
+        Yp = torch.zeros((R_cap, d), dtype=torch.float32, device=DEV)
+        if gather:
+            fe.feplb_grouped_ffn(X, offsets, 0, G, d, f, *wl, H, Yp, AB=AB, row_src=row_src, k=k)
+        else:
+            fe.feplb_grouped_ffn(Xp, offsets, 0, G, d, f, *wl, H, Yp, AB=AB)
+        torch.cuda.synchronize()
+        outs.append((H, AB, Yp))
+    assert all(torch.equal(a, b) for a, b in zip(*outs))
+    # and the plain forward writes the same H and Yp as the training forward
+    H = torch.zeros((R_cap, f), dtype=torch.bfloat16, device=DEV)
+    Yp = torch.zeros((R_cap, d), dtype=torch.float32, device=DEV)
+    fe.feplb_grouped_ffn(Xp, offsets, 0, G, d, f, *wl, H, Yp)
+    torch.cuda.synchronize()
+    assert torch.equal(H, outs[0][0]) and torch.equal(Yp, outs[0][2])
