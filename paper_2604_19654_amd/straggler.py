@@ -123,11 +123,13 @@ class FfnTimer:
 
 def study(P: int, dyn_list: Sequence[int], n_batches: int, tokens_per_rank: int = 16384, E: int = 128,
           k: int = 8, d: int = 6144, f: int = 2048, tau: int = 0, seed0: int = 5000, gemm_dyn: int = 4,
-          device="cuda:0", with_gemm: bool = True, with_backward: bool = False) -> Dict:
+          device="cuda:0", with_gemm: bool = True, with_backward: bool = False,
+          tau_list: Sequence[int] = ()) -> Dict:
     """Mean token straggler before / after the plan for every dyn in dyn_list, and (for
     dyn = gemm_dyn) the mean GEMM straggler before / after, over n_batches micro-batches."""
     T = P * tokens_per_rank
     tok = {"before": [], **{f"dyn{n}": [] for n in dyn_list}}
+    by_tau = {int(t): [] for t in tau_list}        # token straggler after the plan, dyn = gemm_dyn
     gemm = {"before": [], "after": []}
     layer = {"fwd_before": [], "bwd_before": [], "fwd_after": [], "bwd_after": []}
     timer = None
@@ -138,6 +140,8 @@ def study(P: int, dyn_list: Sequence[int], n_batches: int, tokens_per_rank: int 
         torch.cuda.synchronize()
         counts = counts_dev.cpu().numpy().astype(np.int64)
         owner = wl.owner()
+        for t in by_tau:
+            by_tau[t].append(straggler(plan_counts(P, owner, counts, wl.dyn_flags(gemm_dyn), gemm_dyn, t)[2]))
         first = True
         for n in dyn_list:
             moves, before, after = plan_counts(P, owner, counts, wl.dyn_flags(n), n, tau)
@@ -162,6 +166,8 @@ def study(P: int, dyn_list: Sequence[int], n_batches: int, tokens_per_rank: int 
            "token_straggler": {key: float(np.mean(v)) for key, v in tok.items()}}
     base = out["token_straggler"]["before"]
     out["token_reduction_pct"] = {key: 100.0 * (1.0 - v / base) for key, v in out["token_straggler"].items() if key != "before"}
+    if by_tau:
+        out["token_straggler_by_tau"] = {str(t): float(np.mean(v)) for t, v in by_tau.items()}
     if with_gemm and gemm["before"]:
         gb, ga = float(np.mean(gemm["before"])), float(np.mean(gemm["after"]))
         out["gemm_straggler_ms"] = {"before": gb, f"dyn{gemm_dyn}": ga, "d": d, "f": f}
@@ -180,6 +186,8 @@ def main():
     ap.add_argument("--d", type=int, default=6144)
     ap.add_argument("--f", type=int, default=2048)
     ap.add_argument("--tau", type=int, default=0)
+    ap.add_argument("--tau-sweep", type=int, nargs="*", default=[],
+                    help="thresholds tau (minimum rows for an expert to be moved) to sweep at dyn=4")
     ap.add_argument("--no-gemm", action="store_true")
     ap.add_argument("--backward", action="store_true",
                     help="also time every rank's FFN training step (forward keeping the SwiGLU derivatives, backward) and report the slowest rank's times before and after the plan")
@@ -187,7 +195,8 @@ def main():
     B.lib()
     rows = []
     for P in a.ep:
-        r = study(P, a.dyn, a.batches, a.tokens_per_rank, d=a.d, f=a.f, tau=a.tau, with_gemm=not a.no_gemm, with_backward=a.backward)
+        r = study(P, a.dyn, a.batches, a.tokens_per_rank, d=a.d, f=a.f, tau=a.tau, with_gemm=not a.no_gemm, with_backward=a.backward,
+                  tau_list=a.tau_sweep)
         rows.append(r)
         print(json.dumps(r), flush=True)
     print("\n| EP | token straggler before | " + " | ".join(f"dyn={n}" for n in a.dyn) + " | GEMM straggler before (ms) | dyn=4 (ms) |")
@@ -205,6 +214,13 @@ def main():
             m = r.get("slowest_rank_ffn_ms")
             if m:
                 print(f"| {r['P']} | {m['fwd_before']:.2f} / {m['bwd_before']:.2f} | {m['fwd_after']:.2f} / {m['bwd_after']:.2f} |")
+    if a.tau_sweep:
+        print("\n| EP | before | " + " | ".join(f"tau={t}" for t in a.tau_sweep) + " |")
+        print("|---|---|" + "---|" * len(a.tau_sweep))
+        for r in rows:
+            bt = r["token_straggler_by_tau"]
+            base = r["token_straggler"]["before"]
+            print(f"| {r['P']} | {base:.0f} | " + " | ".join(f"{bt[str(t)]:.0f} (-{100 * (1 - bt[str(t)] / base):.0f}%)" for t in a.tau_sweep) + " |")
 
 
 if __name__ == "__main__":
