@@ -55,8 +55,8 @@ const char* feplb_version(void);
 const char* feplb_last_error(void);
 
 /* ------------------------------------------------------------------ routing
- * Section 2.3: "the router produces routing decisions on all devices"; the
- * paper's model uses top-k routing over 128 routed experts with no auxiliary
+ * Section 2.3: every device first runs the router, whose per-token expert choices
+ * drive everything that follows; the paper's model uses top-k routing over 128 routed experts with no auxiliary
  * loss (Section 3.1).  The paper does not give the score function; this build
  * uses softmax over all E logits, keeps the k largest and renormalises them to
  * sum to one.  Selection order: logit descending, expert id ascending on ties
@@ -250,8 +250,8 @@ int32_t feplb_grouped_ffn_backward(const void* Xp, const int32_t* offsets,
                                    void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------ combine
- * Section 2.3: "the Combine phase returns results to source devices"; this is
- * its local part: Y[t,:] = sum over slots j with inv[t*k+j] >= 0 of
+ * Section 2.3: the last step of a micro-batch hands the experts' outputs back to the
+ * tokens' source devices (Combine); this is its local part: Y[t,:] = sum over slots j with inv[t*k+j] >= 0 of
  * topk_w[t,j] * Yp[inv[t*k+j],:], summed in fp32 in ascending j and rounded
  * once to bf16.  Tokens with no local slot get +0.
  *
