@@ -180,3 +180,37 @@ int main(void) {
     assert want in r.stdout, (want, r.stdout)
     assert want == "moves=2 expert=0 0->1 rows=50 before=80,10 after=35,55"     # worked by hand from Section 2.3's rule
     assert f"bytes={72 * 2**20}" in r.stdout
+
+
+def test_plan_latency_fits_the_papers_budget():
+    """Section 2.3 budgets about 50 microseconds of one CPU core for the plan at 128 experts and
+    EP = 8, so that it hides behind the static experts' compute.  Timed through the C ABI on
+    skewed full-size counts; the bound leaves room for a loaded test machine."""
+    import time
+    import workloads
+    wl = workloads.make("C4", T=8192, d=8, f=8)
+    _, _, counts = orc.route_topk(wl.logits.numpy(), wl.k)
+    counts = counts * 16                                   # the full workload's token count
+    L = fe.lib()
+    E, P = 128, 8
+    owner = np.ascontiguousarray(wl.owner(), dtype=np.int32)
+    n = np.ascontiguousarray(counts, dtype=np.int64)
+    dyn = np.ascontiguousarray(wl.dyn_flags(4), dtype=np.uint8)
+    slots = np.full(P, 8, dtype=np.int32)
+    moves = (fe.Move * 64)()
+    n_moves, chosen = C.c_int32(), C.c_int32()
+    before, after = np.zeros(P, dtype=np.int64), np.zeros(P, dtype=np.int64)
+    args = (P, E, *(a.ctypes.data_as(C.c_void_p) for a in (owner, n, dyn, slots)), 64, fe.PLAN_WHOLE, -1, moves, 64,
+            C.byref(n_moves), before.ctypes.data_as(C.c_void_p), after.ctypes.data_as(C.c_void_p), C.byref(chosen))
+
+    def call():
+        return L.feplb_plan(*args)
+    assert call() == 0 and n_moves.value > 0
+    times = []
+    for _ in range(200):
+        t0 = time.perf_counter()
+        call()
+        times.append(time.perf_counter() - t0)
+    med = float(np.median(times)) * 1e6
+    print(f"feplb_plan, E=128, EP=8, {n_moves.value} moves: median {med:.1f} us (ctypes call included)")
+    assert med < 50.0
