@@ -24,7 +24,6 @@ if ROOT not in sys.path:
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 (no sparsity)
 HBM_PEAK_GBPS = 8000.0           # MI355X HBM3E
-HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch of the gate/up GEMM (read + written), measured with rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE and calibrated against the row-copy kernel of the same run; see
 # profiles/hbm_traffic_C4_pmc.md.  Only for the workload it was measured on.

@@ -256,10 +256,13 @@ int32_t feplb_grouped_ffn_backward(const void* Xp, const int32_t* offsets,
  * once to bf16.  Tokens with no local slot get +0.
  *
  *   Yp device [R_cap,d] of yp_dtype; inv device int32 [T*k]; topk_w device fp32 [T,k]
+ *   R_cap rows that Yp holds.  feplb_permute keeps the true row numbers in inv when the
+ *         permutation overflowed its capacity; a slot whose row is >= R_cap was never
+ *         computed, is treated as not local and is never read.
  *   Y  device, bf16 [T,d]  out
  * Limits: d % 8 == 0, k <= FEPLB_MAX_TOPK.
  */
-int32_t feplb_unpermute_combine(const void* Yp, int32_t yp_dtype,
+int32_t feplb_unpermute_combine(const void* Yp, int32_t yp_dtype, int32_t R_cap,
                                 const int32_t* inv, const float* topk_w,
                                 int32_t T, int32_t k, int32_t d, void* Y,
                                 void* stream);
@@ -277,12 +280,14 @@ int32_t feplb_unpermute_combine(const void* Yp, int32_t yp_dtype,
  *
  *   dY      device, bf16 [T,d]
  *   Yp      device, [R_cap,d] of yp_dtype, the expert outputs of the forward pass
+ *   R_cap   rows of Yp and dYp; a slot whose row in inv is >= R_cap counts as not local
+ *           (nothing is read or written for it, its dw is 0)
  *   dYp     device, bf16 [R_cap,d]  out (rows no slot refers to are left alone)
  *   dw      device, fp32 [T,k]      out
  *   dlogits device, fp32 [T,E]      out
  * Limits: d % 8 == 0, k <= FEPLB_MAX_TOPK, E <= FEPLB_MAX_EXPERTS.
  */
-int32_t feplb_combine_backward(const void* dY, const void* Yp, int32_t yp_dtype,
+int32_t feplb_combine_backward(const void* dY, const void* Yp, int32_t yp_dtype, int32_t R_cap,
                                const int32_t* inv, const float* topk_w,
                                int32_t T, int32_t k, int32_t d, void* dYp, float* dw,
                                void* stream);

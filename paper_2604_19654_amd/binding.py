@@ -71,8 +71,8 @@ def lib():
         L.feplb_grouped_ffn_backward.argtypes = [vp, vp, i32, i32, i32, i32, i32, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
                                                  vp, vp, vp, vp, i32, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
                                                  vp, sz, i32, vp, sz, vp]
-        L.feplb_unpermute_combine.argtypes = [vp, i32, vp, vp, i32, i32, i32, vp, vp]
-        L.feplb_combine_backward.argtypes = [vp, vp, i32, vp, vp, i32, i32, i32, vp, vp, vp]
+        L.feplb_unpermute_combine.argtypes = [vp, i32, i32, vp, vp, i32, i32, i32, vp, vp]
+        L.feplb_combine_backward.argtypes = [vp, vp, i32, i32, vp, vp, i32, i32, i32, vp, vp, vp]
         L.feplb_route_topk_backward.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
         L.feplb_stage_weights.argtypes = [vp, vp, sz, vp, vp]
         L.feplb_stream_wait.argtypes = [vp, vp]
@@ -311,7 +311,7 @@ def feplb_unpermute_combine(Yp, inv, topk_w, T, k, d, Y=None, stream=None):
     yp_dtype = {torch.float32: F32, torch.bfloat16: BF16}[Yp.dtype]
     if Y is None:
         Y = torch.empty((T, d), dtype=torch.bfloat16, device=Yp.device)
-    _check(lib().feplb_unpermute_combine(_ptr(Yp), yp_dtype, _ptr(inv), _ptr(topk_w), T, k, d, _ptr(Y),
+    _check(lib().feplb_unpermute_combine(_ptr(Yp), yp_dtype, int(Yp.shape[0]), _ptr(inv), _ptr(topk_w), T, k, d, _ptr(Y),
                                          _stream(stream)), "feplb_unpermute_combine")
     return Y
 
@@ -323,7 +323,9 @@ def feplb_combine_backward(dY, Yp, inv, topk_w, T, k, d, dYp, dw=None, stream=No
     yp_dtype = {torch.float32: F32, torch.bfloat16: BF16}[Yp.dtype]
     if dw is None:
         dw = torch.empty((T, k), dtype=torch.float32, device=dY.device)
-    _check(lib().feplb_combine_backward(_ptr(dY), _ptr(Yp), yp_dtype, _ptr(inv), _ptr(topk_w), T, k, d,
+    if dYp.shape[0] != Yp.shape[0]:
+        raise FeplbError("Yp and dYp must hold the same number of rows")
+    _check(lib().feplb_combine_backward(_ptr(dY), _ptr(Yp), yp_dtype, int(Yp.shape[0]), _ptr(inv), _ptr(topk_w), T, k, d,
                                         _ptr(dYp), _ptr(dw), _stream(stream)), "feplb_combine_backward")
     return dYp, dw
 

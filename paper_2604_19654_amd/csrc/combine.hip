@@ -38,7 +38,7 @@ template <bool YP_BF16, int UNROLL>
 __global__ __launch_bounds__(BLOCK) void combine_kernel(const void* __restrict__ Yp,
                                                         const int* __restrict__ inv,
                                                         const float* __restrict__ w, int T, int k,
-                                                        int d, void* __restrict__ Y) {
+                                                        int d, int R_cap, void* __restrict__ Y) {
   constexpr int PER = YP_BF16 ? 8 : 4;   // values per lane and load
   const int nchunk = d / PER;
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
@@ -49,6 +49,7 @@ __global__ __launch_bounds__(BLOCK) void combine_kernel(const void* __restrict__
   if (lane < k) {
     my_row = inv[t * k + lane];
     my_w = w[t * k + lane];
+    if (my_row >= R_cap) my_row = -1;   // a row past the capacity was never computed: not local
   }
   const unsigned long long local = __ballot(my_row >= 0);
   for (int c0 = 0; c0 < nchunk; c0 += 64 * UNROLL) {
@@ -112,10 +113,10 @@ __global__ __launch_bounds__(BLOCK) void combine_kernel(const void* __restrict__
 
 }  // namespace
 
-extern "C" int32_t feplb_unpermute_combine(const void* Yp, int32_t yp_dtype, const int32_t* inv,
+extern "C" int32_t feplb_unpermute_combine(const void* Yp, int32_t yp_dtype, int32_t R_cap, const int32_t* inv,
                                            const float* topk_w, int32_t T, int32_t k, int32_t d,
                                            void* Y, void* stream) {
-  FEPLB_REQUIRE(T >= 0 && k >= 1 && d >= 0, FEPLB_EINVAL, "combine: negative size");
+  FEPLB_REQUIRE(T >= 0 && k >= 1 && d >= 0 && R_cap >= 0, FEPLB_EINVAL, "combine: negative size");
   FEPLB_REQUIRE(k <= FEPLB_MAX_TOPK, FEPLB_ESHAPE, "combine: k=%d above %d", k, FEPLB_MAX_TOPK);
   FEPLB_REQUIRE(d % 8 == 0, FEPLB_ESHAPE, "combine: d=%d not a multiple of 8", d);
   FEPLB_REQUIRE(yp_dtype == FEPLB_F32 || yp_dtype == FEPLB_BF16, FEPLB_EINVAL,
@@ -124,12 +125,12 @@ extern "C" int32_t feplb_unpermute_combine(const void* Yp, int32_t yp_dtype, con
   FEPLB_REQUIRE(inv && topk_w && Y, FEPLB_EINVAL, "combine: null buffer");
   FEPLB_REQUIRE(feplb::aligned16(Y) && feplb::aligned16(Yp), FEPLB_EALIGN,
                 "combine: Y/Yp not 16-byte aligned");
-  // Yp may be NULL only if no assignment is local; the kernel then never reads it.
+  FEPLB_REQUIRE(Yp || R_cap == 0, FEPLB_EINVAL, "combine: null Yp with R_cap=%d", R_cap);
   hipStream_t s = (hipStream_t)stream;
   const int blocks = (T + WAVES - 1) / WAVES;
   const int per_lane = (d / (yp_dtype == FEPLB_BF16 ? 8 : 4) + 63) / 64;   // 16-byte loads per lane and row
 #define FEPLB_COMBINE(BF, U) \
-  hipLaunchKernelGGL((combine_kernel<BF, U>), dim3(blocks), dim3(BLOCK), 0, s, Yp, inv, topk_w, T, k, d, Y)
+  hipLaunchKernelGGL((combine_kernel<BF, U>), dim3(blocks), dim3(BLOCK), 0, s, Yp, inv, topk_w, T, k, d, R_cap, Y)
   if (yp_dtype == FEPLB_BF16) {
     if (per_lane <= 4) FEPLB_COMBINE(true, 4);
     else if (per_lane <= 8) FEPLB_COMBINE(true, 8);

@@ -26,7 +26,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 template <bool YP_BF16, int UNROLL>
 __global__ __launch_bounds__(BLOCK) void combine_backward_kernel(
     const u32x4* __restrict__ dY, const void* __restrict__ Yp, const int* __restrict__ inv,
-    const float* __restrict__ w, int T, int k, int d, u32x4* __restrict__ dYp, float* __restrict__ dw) {
+    const float* __restrict__ w, int T, int k, int d, int R_cap, u32x4* __restrict__ dYp,
+    float* __restrict__ dw) {
   const int nchunk = d / 8;
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
   const long long t = (long long)blockIdx.x * WAVES + wave;
@@ -36,6 +37,7 @@ __global__ __launch_bounds__(BLOCK) void combine_backward_kernel(
   if (lane < k) {
     my_row = inv[t * k + lane];
     my_w = w[t * k + lane];
+    if (my_row >= R_cap) my_row = -1;   // a row past the capacity does not exist in Yp / dYp
     if (my_row < 0) dw[t * k + lane] = 0.f;
   }
   const u32x4* g_row = dY + t * nchunk;
@@ -121,10 +123,11 @@ __global__ __launch_bounds__(256) void route_backward_kernel(const int* __restri
 
 }  // namespace
 
-extern "C" int32_t feplb_combine_backward(const void* dY, const void* Yp, int32_t yp_dtype, const int32_t* inv,
+extern "C" int32_t feplb_combine_backward(const void* dY, const void* Yp, int32_t yp_dtype, int32_t R_cap,
+                                          const int32_t* inv,
                                           const float* topk_w, int32_t T, int32_t k, int32_t d, void* dYp,
                                           float* dw, void* stream) {
-  FEPLB_REQUIRE(T >= 0 && k >= 1 && d >= 0, FEPLB_EINVAL, "combine_backward: negative size");
+  FEPLB_REQUIRE(T >= 0 && k >= 1 && d >= 0 && R_cap >= 0, FEPLB_EINVAL, "combine_backward: negative size");
   FEPLB_REQUIRE(k <= FEPLB_MAX_TOPK, FEPLB_ESHAPE, "combine_backward: k=%d above %d", k, FEPLB_MAX_TOPK);
   FEPLB_REQUIRE(d % 8 == 0, FEPLB_ESHAPE, "combine_backward: d=%d not a multiple of 8", d);
   FEPLB_REQUIRE(yp_dtype == FEPLB_F32 || yp_dtype == FEPLB_BF16, FEPLB_EINVAL,
@@ -133,14 +136,14 @@ extern "C" int32_t feplb_combine_backward(const void* dY, const void* Yp, int32_
   FEPLB_REQUIRE(dY && inv && topk_w && dw, FEPLB_EINVAL, "combine_backward: null buffer");
   FEPLB_REQUIRE(feplb::aligned16(dY) && feplb::aligned16(Yp) && feplb::aligned16(dYp), FEPLB_EALIGN,
                 "combine_backward: dY/Yp/dYp not 16-byte aligned");
-  // Yp and dYp may be NULL only if no assignment is local; the kernel then never touches them.
+  FEPLB_REQUIRE((Yp && dYp) || R_cap == 0, FEPLB_EINVAL, "combine_backward: null Yp/dYp with R_cap=%d", R_cap);
   hipStream_t s = (hipStream_t)stream;
   const int blocks = (T + WAVES - 1) / WAVES;
   // as many 16-byte pieces of the gradient row per lane as one pass over the row needs, up to 16
   const int per_lane = (d / 8 + 63) / 64;
 #define FEPLB_COMBINE_BWD(BF, U)                                                                             \
   hipLaunchKernelGGL((combine_backward_kernel<BF, U>), dim3(blocks), dim3(BLOCK), 0, s, (const u32x4*)dY, Yp, \
-                     inv, topk_w, T, k, d, (u32x4*)dYp, dw)
+                     inv, topk_w, T, k, d, R_cap, (u32x4*)dYp, dw)
   if (yp_dtype == FEPLB_BF16) {
     if (per_lane <= 4) FEPLB_COMBINE_BWD(true, 4);
     else if (per_lane <= 8) FEPLB_COMBINE_BWD(true, 8);

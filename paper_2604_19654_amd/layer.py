@@ -75,6 +75,12 @@ class RankLayer:
         self.timeline: Dict[str, B.HipEvent] = {}
 
     # -- helpers ---------------------------------------------------------
+    def rows_overflow(self, G: int) -> int:
+        """Rows of the last permutation over G groups beyond the layer's capacity (0: all fit).
+        Reads offsets[G] back, so it synchronises; rows past the capacity are neither computed
+        nor combined (their slots count as not local), which is safe but drops work."""
+        return max(0, int(self.buf.offsets[G].item()) - self.R_cap)
+
     def _mark(self, name: str, on: bool):
         if on:
             ev = self.timeline.get(name)

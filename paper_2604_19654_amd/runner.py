@@ -42,14 +42,17 @@ def _route_counts(wl) -> np.ndarray:
 
 
 def prepare(name: str, device="cuda:0", yp_dtype=torch.float32, source_kind="device", fused_gather=True,
-            **override) -> Prepared:
+            r_cap: Optional[int] = None, **override) -> Prepared:
     """yp_dtype: type of the expert outputs between the down GEMM and the combine: fp32 (default)
     or bf16, which is faster (half the bytes through the down epilogue and the combine) but adds a
     rounding per expert output.
     fused_gather: the gate/up GEMM gathers the token rows itself (no permuted copy of X).
     source_kind: where the replicas' weights are copied from -- "device"
     (a second buffer in HBM, standing in for a peer GPU's memory) or "pinned"
-    (page-locked host memory)."""
+    (page-locked host memory).
+    r_cap: rows the layer's buffers hold.  Default: exactly the rows of this batch, which is
+    right as long as the same logits are stepped; a caller that feeds other batches through the
+    same layer passes a bound (T*k always suffices) and may ask `layer.rows_overflow()`."""
     wl = workloads.make(name, device=device, **override)
     counts = _route_counts(wl)
     if wl.n_dyn == 0:
@@ -57,7 +60,7 @@ def prepare(name: str, device="cuda:0", yp_dtype=torch.float32, source_kind="dev
         groups = [(e, 0, B.ORD_MAX) for e in experts]
         R = int(counts[experts].sum())
         weights = [wl.expert_weights(e) for e in experts]
-        layer = RankLayer(wl.T, wl.E, wl.k, wl.d, wl.f, R_cap=max(R, 1), G_cap=len(groups), device=device,
+        layer = RankLayer(wl.T, wl.E, wl.k, wl.d, wl.f, R_cap=r_cap or max(R, 1), G_cap=len(groups), device=device,
                           yp_dtype=yp_dtype, fused_gather=fused_gather)
         return Prepared(wl, layer, False, groups, weights, wl.rank, R, counts)
     # rebalanced share: the library's plan picks the receiving rank and the replicas
@@ -76,7 +79,7 @@ def prepare(name: str, device="cuda:0", yp_dtype=torch.float32, source_kind="dev
             host.copy_(flat)
             flat = host
         remote[int(e)] = flat
-    layer = RankLayer(wl.T, wl.E, wl.k, wl.d, wl.f, R_cap=max(R, 1), G_cap=len(static) + wl.n_dyn,
+    layer = RankLayer(wl.T, wl.E, wl.k, wl.d, wl.f, R_cap=r_cap or max(R, 1), G_cap=len(static) + wl.n_dyn,
                       device=device, yp_dtype=yp_dtype, n_slots=wl.n_dyn, fused_gather=fused_gather)
     groups = [(e, 0, B.ORD_MAX) for e in static] + [(m[0], m[4], m[4] + m[3]) for m in moves]
     return Prepared(wl, layer, True, groups, [], rank, R, counts, dyn_flag, slots, static_weights, remote,

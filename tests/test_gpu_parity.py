@@ -372,6 +372,46 @@ def test_combine_parity(T, k, d, yp_dtype):
         assert np.all(Y[t].cpu().view(torch.int16).numpy() == 0)       # +0, all bits clear
 
 
+def test_combine_and_its_backward_stay_inside_a_capacity_below_the_row_count():
+    # a permutation that overflows its capacity keeps the true row numbers in inv; the combine and
+    # its backward must treat rows >= R_cap as not local: never read, never written, dw = 0
+    T, E, k, d = 400, 16, 4, 264
+    rng = np.random.default_rng(21)
+    ids = np.stack([rng.permutation(E)[:k] for _ in range(T)]).astype(np.int32)
+    groups = [(e, 0, fe.ORD_MAX) for e in (0, 3, 5, 6, 11, 12)]
+    offsets_o, row_src_o, inv_o = orc.permute(ids, groups)
+    R = int(offsets_o[-1])
+    R_cap = R // 2 + 3
+    assert 0 < R_cap < R
+    _, offsets, row_src, inv = fe.feplb_permute(torch.from_numpy(ids).to(DEV), E, groups, None, R_cap)
+    torch.cuda.synchronize()
+    assert np.array_equal(inv.cpu().numpy(), inv_o) and int(offsets[-1].item()) == R
+    guard = 64
+    gen = torch.Generator().manual_seed(5)
+    w = (torch.rand((T, k), generator=gen) + 0.05).to(DEV)
+    dY = torch.randn((T, d), generator=gen).to(torch.bfloat16).to(DEV)
+    inv_cut = np.where(inv_o >= R_cap, -1, inv_o).astype(np.int32)
+    for yp_dtype in (torch.float32, torch.bfloat16):
+        full = torch.full((R_cap + guard, d), float("nan"), dtype=yp_dtype, device=DEV)
+        full[:R_cap] = torch.randn((R_cap, d), generator=gen).to(yp_dtype).to(DEV)
+        Yp = full[:R_cap]
+        Y = fe.feplb_unpermute_combine(Yp, inv, w, T, k, d)
+        torch.cuda.synchronize()
+        want = orc.combine(f64(Yp), inv_cut, f64(w), T, k)
+        got = f64(Y)
+        assert np.isfinite(got).all(), "a row past the capacity was read"
+        assert np.all(np.abs(got - want) <= 2.0**-8 * np.abs(want) + 1e-6)
+        dfull = torch.full((R_cap + guard, d), 512.0, dtype=torch.bfloat16, device=DEV)
+        dYp, dw = fe.feplb_combine_backward(dY, Yp, inv, w, T, k, d, dfull[:R_cap])
+        torch.cuda.synchronize()
+        assert (dfull[R_cap:].float() == 512.0).all(), "a row past the capacity was written"
+        dYp_o, dw_o = orc.combine_backward(f64(dY), f64(Yp), inv_cut, f64(w), T, k)
+        assert bf16_rounding_excess(f64(dYp), dYp_o) <= 1.0
+        assert np.isfinite(f64(dw)).all() and not f64(dw)[inv_cut.reshape(T, k) < 0].any()
+        scale = np.abs(dw_o).max() + 1.0
+        assert np.abs(f64(dw) - dw_o).max() <= 1e-4 * scale
+
+
 # ------------------------------------------------------------------ whole layer, reduced sizes
 def oracle_layer(p, Y):
     """Runs the oracle on the prepared workload and compares every output of the
@@ -463,9 +503,9 @@ def test_rebalanced_layer_parity_reduced(source_kind, fused_gather):
 
 
 def test_output_does_not_depend_on_where_an_experts_rows_run():
-    # Section 2.2: each token is still processed by the same expert with identical weights, so
-    # splitting an expert's batch between its owner's group and a replica's group (a copy of the
-    # weights) must not change any token's result.  Bit-identical here, because a row's arithmetic
+    # Section 2.2 (exact semantics): a replica holds a byte copy of the owner's matrices, so
+    # splitting an expert's batch between its owner's group and a replica's group
+    # must not change any token's result.  Bit-identical here, because a row's arithmetic
     # does not depend on which tile it sits in.
     p = runner.prepare("C3", DEV, T=2048, d=512, f=256)
     Y_whole = runner.step(p).clone()
@@ -568,7 +608,8 @@ def test_misaligned_and_small_workspace_are_refused():
 def test_graph_replay_of_the_static_step_equals_the_eager_step():
     # several replays, each after new inputs were copied into the captured buffers and with eager
     # work and synchronisations in between; every replay against the eager step on the same inputs
-    p = runner.prepare("C2", DEV, T=1536, d=512, f=384)
+    # the replays route new logits through the captured buffers: size them for any routing
+    p = runner.prepare("C2", DEV, T=1536, d=512, f=384, r_cap=1536 * 8)
     wl, lay = p.wl, p.layer
     runner.step(p)
     torch.cuda.synchronize()
@@ -588,4 +629,5 @@ def test_graph_replay_of_the_static_step_equals_the_eager_step():
         torch.cuda.synchronize()
         assert torch.equal(lay.buf.topk_ids, ids_eager), f"replay {it}: routing differs"
         assert torch.equal(lay.buf.Y, eager), f"replay {it}: output differs"
+        assert lay.rows_overflow(len(p.groups)) == 0
         (lay.buf.Y.float().sum() + wl.X.float().sum()).item()        # eager library work between replays

@@ -42,8 +42,8 @@ def test_argument_validation_happens_before_any_device_work():
     assert L.feplb_route_topk(None, 4, 4000, 2, None, None, None, None) == -2    # E above the limit
     assert L.feplb_route_topk(None, -1, 4, 2, None, None, None, None) == -1
     assert b"route_topk" in L.feplb_last_error()
-    assert L.feplb_unpermute_combine(None, 0, None, None, 4, 2, 12, None, None) == -2   # d % 8
-    assert L.feplb_unpermute_combine(None, 7, None, None, 4, 2, 16, None, None) == -1   # dtype
+    assert L.feplb_unpermute_combine(None, 0, 0, None, None, 4, 2, 12, None, None) == -2   # d % 8
+    assert L.feplb_unpermute_combine(None, 7, 0, None, None, 4, 2, 16, None, None) == -1   # dtype
     g = (fe.Group * 2)(fe.Group(0, 0, 10), fe.Group(0, 5, 20))
     rc = L.feplb_permute(None, 0, 2, 4, g, 2, None, 0, None, 0, 16, None, None, None, 0, None)
     assert rc == -1 and b"overlap" in L.feplb_last_error()
@@ -68,9 +68,9 @@ def test_argument_validation_happens_before_any_device_work():
     assert fe.binding.feplb_grouped_ffn_backward_wt_bytes(20, 6144, 2048) == 20 * 72 * 2**20   # one transposed copy of every expert
     assert L.feplb_grouped_ffn_train(None, None, 0, 0, None, 0, 1, 128, 256, 128, None, None, None, None, None, None,
                                      0, 7, None, 0, None) == -1                          # keeping the derivatives needs the AB buffer
-    assert L.feplb_combine_backward(None, None, 0, None, None, 4, 2, 12, None, None, None) == -2     # d % 8
-    assert L.feplb_combine_backward(None, None, 9, None, None, 4, 2, 16, None, None, None) == -1     # dtype
-    assert L.feplb_combine_backward(None, None, 0, None, None, 0, 2, 16, None, None, None) == 0      # no tokens
+    assert L.feplb_combine_backward(None, None, 0, 0, None, None, 4, 2, 12, None, None, None) == -2     # d % 8
+    assert L.feplb_combine_backward(None, None, 9, 0, None, None, 4, 2, 16, None, None, None) == -1     # dtype
+    assert L.feplb_combine_backward(None, None, 0, 0, None, None, 0, 2, 16, None, None, None) == 0      # no tokens
     assert L.feplb_route_topk_backward(None, None, None, 4, 4, 5, None, None) == -2                  # k > E
     assert L.feplb_route_topk_backward(None, None, None, 4, 8, 2, None, None) == -1                  # null buffers
     assert fe.feplb_permute_workspace_bytes(1024, 8, 128, 20) > 0
