@@ -181,6 +181,30 @@ int32_t feplb_grouped_ffn(const void* Xp, const int32_t* row_src, int32_t T, int
                           void* H, void* Yp, int32_t yp_dtype, int32_t phases,
                           void* ws, size_t ws_bytes, void* stream);
 
+/* The same call for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * results and limits as feplb_grouped_ffn, without ws / ws_bytes: the tile table lives in
+ * FEPLB_STATIC_WS_BYTES of device memory that is part of the library itself (each GPU the library
+ * runs on holds its own copy until the process ends).  Nothing is allocated or freed, by the
+ * library or through any routine it calls.
+ *   - Refused with FEPLB_ESHAPE when feplb_grouped_ffn_workspace_bytes(R_cap, g_end - g_begin)
+ *     exceeds FEPLB_STATIC_WS_BYTES (256 KiB: about 4.1 million rows in 128 groups).
+ *   - Every call on one GPU shares that GPU's table.  SCHEDULE rewrites the part it uses, so a
+ *     later call with another range or fewer rows is safe; a GEMM phase without SCHEDULE runs on
+ *     the table the last SCHEDULE on this GPU left.  Calls that overlap on one GPU (two streams,
+ *     two threads) race on the table: order them.
+ */
+#define FEPLB_STATIC_WS_BYTES 262144
+
+int32_t feplb_grouped_ffn_static(const void* Xp, const int32_t* row_src, int32_t T, int32_t k,
+                                 const int32_t* offsets,
+                                 int32_t g_begin, int32_t g_end, int32_t R_cap,
+                                 int32_t d, int32_t f,
+                                 const void* const* w_gate, const void* const* w_up,
+                                 const void* const* w_down,
+                                 void* H, void* Yp, int32_t yp_dtype, int32_t phases,
+                                 void* stream);
+
 /* ------------------------------------------------------------------ expert FFN, training
  * Section 3.2 reports the MoE layer's time per forward AND backward pass; the
  * backward of the Grouped GEMM of Section 3.1 is again grouped GEMMs over the same

@@ -4,7 +4,7 @@ from .binding import (  # noqa: F401
     FeplbError, Group, Move, ORD_MAX, F32, BF16, FFN_GATE_UP, FFN_DOWN, FFN_SCHEDULE, FFN_ALL,
     PLAN_WHOLE, PLAN_OVERFLOW, lib, lib_path, version, HipEvent,
     feplb_route_topk, feplb_permute, feplb_permute_workspace_bytes,
-    feplb_grouped_ffn, feplb_grouped_ffn_workspace_bytes,
+    feplb_grouped_ffn, feplb_grouped_ffn_workspace_bytes, feplb_grouped_ffn_static, STATIC_WS_BYTES,
     feplb_unpermute_combine, feplb_stage_weights, feplb_stream_wait,
     feplb_expert_bytes, feplb_plan,
     BWD_SCHEDULE, BWD_TRANSPOSE, BWD_DGRAD, BWD_WGRAD, BWD_ALL, BWD_ACCUMULATE,

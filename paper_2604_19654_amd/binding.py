@@ -64,6 +64,8 @@ def lib():
         L.feplb_grouped_ffn_workspace_bytes.restype = sz
         L.feplb_grouped_ffn.argtypes = [vp, vp, i32, i32, vp, i32, i32, i32, i32, i32, C.POINTER(vp), C.POINTER(vp),
                                         C.POINTER(vp), vp, vp, i32, i32, vp, sz, vp]
+        L.feplb_grouped_ffn_static.argtypes = [vp, vp, i32, i32, vp, i32, i32, i32, i32, i32, C.POINTER(vp), C.POINTER(vp),
+                                               C.POINTER(vp), vp, vp, i32, i32, vp]
         L.feplb_grouped_ffn_train.argtypes = [vp, vp, i32, i32, vp, i32, i32, i32, i32, i32, C.POINTER(vp), C.POINTER(vp),
                                               C.POINTER(vp), vp, vp, vp, i32, i32, vp, sz, vp]
         L.feplb_grouped_ffn_backward_wt_bytes.argtypes = [i32, i32, i32]
@@ -80,7 +82,7 @@ def lib():
         L.feplb_expert_bytes.restype = sz
         L.feplb_plan.argtypes = [i32, i32, vp, vp, vp, vp, i64, i32, i32, C.POINTER(Move), i32,
                                  C.POINTER(i32), vp, vp, C.POINTER(i32)]
-        for name in ("feplb_route_topk", "feplb_permute", "feplb_permute_append", "feplb_grouped_ffn", "feplb_grouped_ffn_train",
+        for name in ("feplb_route_topk", "feplb_permute", "feplb_permute_append", "feplb_grouped_ffn", "feplb_grouped_ffn_static", "feplb_grouped_ffn_train",
                      "feplb_grouped_ffn_backward", "feplb_unpermute_combine", "feplb_combine_backward",
                      "feplb_route_topk_backward",
                      "feplb_stage_weights", "feplb_stream_wait", "feplb_plan"):
@@ -276,6 +278,25 @@ def feplb_grouped_ffn(Xp, offsets, g_begin, g_end, d, f, w_gate, w_up, w_down, H
                                    _ptr_array(w_gate), _ptr_array(w_up), _ptr_array(w_down),
                                    _ptr(H), _ptr(Yp), yp_dtype, phases, _ptr(ws), ws.numel(),
                                    _stream(stream)), "feplb_grouped_ffn")
+    return H, Yp
+
+
+STATIC_WS_BYTES = 262144   # FEPLB_STATIC_WS_BYTES
+
+
+def feplb_grouped_ffn_static(Xp, offsets, g_begin, g_end, d, f, w_gate, w_up, w_down, H, Yp,
+                             phases=FFN_ALL, stream=None, row_src=None, k=0):
+    """feplb_grouped_ffn without a workspace: the tile table lives in device memory that is part of
+    the library (for callers that cannot allocate).  Same arguments and results otherwise."""
+    R_cap = H.shape[0]
+    yp_dtype = F32
+    if Yp is not None:
+        yp_dtype = {torch.float32: F32, torch.bfloat16: BF16}[Yp.dtype]
+    n_src = int(Xp.shape[0]) if row_src is not None else 0
+    _check(lib().feplb_grouped_ffn_static(_ptr(Xp), _ptr(row_src), n_src, k, _ptr(offsets), g_begin, g_end, R_cap, d, f,
+                                          _ptr_array(w_gate), _ptr_array(w_up), _ptr_array(w_down),
+                                          _ptr(H), _ptr(Yp), yp_dtype, phases, _stream(stream)),
+           "feplb_grouped_ffn_static")
     return H, Yp
 
 

@@ -39,6 +39,7 @@
 // Blocks are mapped to tiles in 8 x 4 patches per XCD (workgroups are dealt
 // round-robin to the 8 XCDs, each with its own L2), so the 32 tiles an XCD
 // runs at a time share 8 row panels and 4 weight panels.
+#include <mutex>
 #include <type_traits>
 #include "common.h"
 #include "gemm_device.h"
@@ -657,6 +658,51 @@ extern "C" int32_t feplb_grouped_ffn(const void* Xp, const int32_t* row_src, int
                                      void* stream) {
   return forward_impl(Xp, row_src, T, k, offsets, g_begin, g_end, R_cap, d, f, w_gate, w_up, w_down, H,
                       nullptr, Yp, yp_dtype, phases, ws, ws_bytes, stream);
+}
+
+// ---- the forward call for callers that cannot allocate: its tile table lives in device memory
+// that belongs to the library's code object instead of a caller's workspace
+namespace {
+static __device__ __align__(256) unsigned char scratch[FEPLB_STATIC_WS_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+void* g_scratch_ptr[MAX_DEVICES];   // this process's address of `scratch` on each device, once known
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device.  In host code the array's name is only a
+// handle for the runtime, not a device address: every use below goes through this pointer.
+int32_t static_scratch(void** out) {
+  int dev = -1;
+  FEPLB_HIP(hipGetDevice(&dev));
+  FEPLB_REQUIRE(dev >= 0 && dev < MAX_DEVICES, FEPLB_ESHAPE, "grouped_ffn_static: device %d above %d", dev, MAX_DEVICES);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    FEPLB_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    FEPLB_REQUIRE(p && feplb::aligned16(p), FEPLB_EHIP, "grouped_ffn_static: no device address for the scratch array");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return FEPLB_OK;
+}
+}  // namespace
+
+extern "C" int32_t feplb_grouped_ffn_static(const void* Xp, const int32_t* row_src, int32_t T, int32_t k,
+                                            const int32_t* offsets, int32_t g_begin, int32_t g_end,
+                                            int32_t R_cap, int32_t d, int32_t f, const void* const* w_gate,
+                                            const void* const* w_up, const void* const* w_down, void* H,
+                                            void* Yp, int32_t yp_dtype, int32_t phases, void* stream) {
+  FEPLB_REQUIRE(g_begin >= 0 && g_end >= g_begin && R_cap >= 0, FEPLB_EINVAL,
+                "grouped_ffn_static: negative size or empty range reversed");
+  const size_t need = feplb_grouped_ffn_workspace_bytes(R_cap, g_end - g_begin);
+  FEPLB_REQUIRE(need <= (size_t)FEPLB_STATIC_WS_BYTES, FEPLB_ESHAPE,
+                "grouped_ffn_static: R_cap=%d rows in %d groups need %zu bytes of tile table, the built-in scratch "
+                "holds %d; use feplb_grouped_ffn with a workspace", R_cap, g_end - g_begin, need, FEPLB_STATIC_WS_BYTES);
+  void* ws = nullptr;
+  const int32_t rc = static_scratch(&ws);
+  if (rc != FEPLB_OK) return rc;
+  return forward_impl(Xp, row_src, T, k, offsets, g_begin, g_end, R_cap, d, f, w_gate, w_up, w_down, H,
+                      nullptr, Yp, yp_dtype, phases, ws, FEPLB_STATIC_WS_BYTES, stream);
 }
 
 extern "C" int32_t feplb_grouped_ffn_train(const void* Xp, const int32_t* row_src, int32_t T, int32_t k,
