@@ -71,3 +71,67 @@ def bf16_rounding_excess(got: np.ndarray, want: np.ndarray) -> float:
     rms = np.sqrt((want ** 2).mean(axis=1, keepdims=True))
     allowed = 2.0 ** -8 * np.abs(want) + 1e-3 * rms + 1e-30
     return float((np.abs(got - want) / allowed).max())
+
+
+# ---------------------------------------------------------------------------------------------
+# What the storage formats of the path cost, element by element.
+#
+# The path keeps two tensors in bf16 on purpose: the SwiGLU activations H (they are the down
+# GEMM's MFMA operand) and the layer's output Y.  Everything else is fp32 (accumulators, expert
+# outputs Yp, the combine's sum).  Against the unrounded float64 oracle an element of Y therefore
+# carries
+#   (1) the output rounding: at most half a bf16 step of the value that is rounded,
+#       hu(v) = 2^(floor(log2 |v|) - 8);
+#   (2) the H roundings, pushed through the down projection and the combine:
+#       e_i = sum_j w_j sum_f dH[j,f] Wd_j[f,i] with |dH[j,f]| <= hu(H[j,f]).  The roundings of
+#       different elements are independent and, to the accuracy needed here, uniform in their
+#       interval (variance hu^2 / 3), so e_i is a sum of thousands of independent bounded terms
+#       with standard deviation sigma_i = sqrt( sum_j w_j^2 sum_f hu(H[j,f])^2 / 3 * Wd_j[f,i]^2 );
+#   (3) fp32 accumulation and the hardware exponential / reciprocal: relative 1e-5 at most,
+#       carried as 1e-5 |Y_i| and as a 2 % widening of sigma (H is rounded from an fp32 value
+#       that is itself off by that much).
+# Bound per element: hu(|Y_i| + n sigma_i) + n sigma_i + 1e-5 |Y_i| with n = 7 (a Gaussian tail
+# of 3e-12 per element; the largest check looks at 4e8 elements).
+# ---------------------------------------------------------------------------------------------
+FORMAT_NSIGMA = 7.0
+
+
+def bf16_half_ulp(v: np.ndarray) -> np.ndarray:
+    """Half the spacing of bf16 numbers around |v| (8 significand bits): 2^(floor(log2|v|) - 8)."""
+    a = np.maximum(np.abs(v), 2.0 ** -126)
+    return np.exp2(np.floor(np.log2(a)) - 8.0)
+
+
+def h_rounding_variance(orc, x_rows: np.ndarray, weights) -> tuple:
+    """For rows x of one expert: the oracle's (H, Yp) and, per element of Yp, the variance of the
+    error that rounding H to bf16 causes: (hu(H)^2 / 3) @ (Wd^2)."""
+    h, y = orc.ffn_rows(x_rows, *weights)
+    wd = np.asarray(weights[2], dtype=np.float64)
+    return h, y, (bf16_half_ulp(h) ** 2 / 3.0) @ (wd * wd)
+
+
+def format_bound(value: np.ndarray, variance: np.ndarray, output_bf16: bool) -> np.ndarray:
+    """Element-wise bound described above for a result `value` whose H-rounding variance is given."""
+    ns = FORMAT_NSIGMA * 1.02 * np.sqrt(variance)
+    b = ns + 1e-5 * np.abs(value) + 1e-30
+    if output_bf16:
+        b = b + bf16_half_ulp(np.abs(value) + ns)
+    return b
+
+
+def layer_tokens_with_format_bound(orc, x_rows, ids_rows, w_rows, keep_rows, weights_of):
+    """The layer's result for a batch of tokens, expert by expert like orc.moe_tokens, together
+    with the element-wise format bound of Y.  Returns (Y [m,d], bound [m,d])."""
+    x = np.asarray(x_rows, dtype=np.float64)
+    ids_rows = np.asarray(ids_rows)
+    keep_rows = np.asarray(keep_rows, dtype=bool)
+    w_rows = np.asarray(w_rows, dtype=np.float64)
+    out = np.zeros_like(x)
+    var = np.zeros_like(x)
+    for e in sorted(set(int(v) for v in ids_rows[keep_rows])):
+        tok, slot = np.nonzero((ids_rows == e) & keep_rows)      # a token names an expert at most once
+        _, y, v = h_rounding_variance(orc, x[tok], weights_of(e))
+        wj = w_rows[tok, slot][:, None]
+        out[tok] += wj * y
+        var[tok] += wj * wj * v
+    return out, format_bound(out, var, output_bf16=True)
