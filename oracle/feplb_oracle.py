@@ -34,6 +34,13 @@ What each function follows:
                     Parity unpinned against the paper; invariants only.
   pick_receiver     workload convention, not in the paper.  Parity unpinned.
   token_straggler   Section 3.1 Metrics.
+  history_update, place_lpt, mark_dynamic   Section 2.3, macro level: a Router
+                    Predictor re-assigns experts to devices from routing history,
+                    now and then.  The paper names it and gives no algorithm; the
+                    rule here (exponential moving average of the counts, longest
+                    processing time first under a per-device expert limit, kept
+                    only when it lowers the predicted maximum, bins named so that
+                    few experts migrate) is this build's reading.
   experts_per_device, dynamic_buffer_bytes   Section 2.3 worked numbers.
 """
 from __future__ import annotations
@@ -378,6 +385,96 @@ def token_straggler(loads) -> float:
     """max over ranks of the token count minus the mean (Section 3.1 Metrics)."""
     L = np.asarray(loads, dtype=np.float64)
     return float(L.max() - L.mean())
+
+
+# --------------------------------------------------------------------------
+# macro level: placement from routing history
+# --------------------------------------------------------------------------
+HIST_FRAC_BITS = 16
+
+
+def history_update(hist, n, shift: int) -> np.ndarray:
+    """Exponential moving average of the per-expert counts in fixed point (units of
+    2^-16 rows, so that every device computes the same integers):
+        hist[e] <- hist[e] + floor(((n[e] << 16) - hist[e]) / 2^shift),
+    i.e. decay 1 - 2^-shift per micro-batch; shift = 0 keeps the last batch only."""
+    if shift < 0 or shift > 30:
+        raise ValueError("shift out of range")
+    out = np.zeros(len(n), dtype=np.int64)
+    for e in range(len(n)):
+        h = int(hist[e])
+        out[e] = h + (((int(n[e]) << HIST_FRAC_BITS) - h) // (1 << shift))     # Python's // floors
+    return out
+
+
+def place_lpt(P: int, hist, cap: int, owner_in):
+    """New expert -> rank map from the history.  Longest processing time first: experts in
+    order of history, largest first (lowest id on ties), each to the bin with the least
+    accumulated history among the bins that hold fewer than `cap` experts (lowest bin on
+    ties).  The result replaces the current map only if its largest bin is strictly below the
+    current map's largest rank load (migration costs a weight transfer per expert).  Bins
+    are then named after ranks so that many experts stay: repeatedly give the (bin, rank)
+    pair that shares the most experts, among bins and ranks not yet paired (lowest bin, then
+    lowest rank on ties), to each other.
+    Returns (owner_out [E] int32, load_before [P], load_after [P], migrated)."""
+    E = len(hist)
+    if cap * P < E:
+        raise ValueError("cap * P < E")
+    owner_in = np.asarray(owner_in, dtype=np.int32)
+    before = rank_loads(P, owner_in, hist)
+    order = sorted(range(E), key=lambda e: (-int(hist[e]), e))
+    load = [0] * P
+    held = [0] * P
+    bin_of = [0] * E
+    for e in order:
+        best = -1
+        for b in range(P):
+            if held[b] < cap and (best < 0 or load[b] < load[best]):
+                best = b
+        bin_of[e] = best
+        load[best] += int(hist[e])
+        held[best] += 1
+    if E == 0 or max(load) >= int(before.max()):
+        return owner_in.copy(), before, before.copy(), 0
+    shared = [[0] * P for _ in range(P)]
+    for e in range(E):
+        shared[bin_of[e]][int(owner_in[e])] += 1
+    rank_of = [-1] * P
+    taken = [False] * P
+    for _ in range(P):
+        pick = None
+        for b in range(P):
+            if rank_of[b] >= 0:
+                continue
+            for r in range(P):
+                if not taken[r] and (pick is None or shared[b][r] > shared[pick[0]][pick[1]]):
+                    pick = (b, r)
+        rank_of[pick[0]] = pick[1]
+        taken[pick[1]] = True
+    owner_out = np.array([rank_of[bin_of[e]] for e in range(E)], dtype=np.int32)
+    after = rank_loads(P, owner_out, hist)
+    return owner_out, before, after, int((owner_out != owner_in).sum())
+
+
+def mark_dynamic(P: int, owner, hist, dyn: int) -> np.ndarray:
+    """[E] uint8: on every rank its `dyn` experts with the largest history (lowest id on
+    ties) are the dynamic ones (Section 2.3 gives only their number)."""
+    E = len(hist)
+    flag = np.zeros(E, dtype=np.uint8)
+    for r in range(P):
+        mine = [e for e in range(E) if int(owner[e]) == r]
+        mine.sort(key=lambda e: (-int(hist[e]), e))
+        for e in mine[:dyn]:
+            flag[e] = 1
+    return flag
+
+
+def apply_moves(owner, moves) -> np.ndarray:
+    """Rank that runs each expert once the whole-expert moves of a plan are applied."""
+    home = np.asarray(owner, dtype=np.int32).copy()
+    for (e, _src, dst, _rows, _lo) in moves:
+        home[int(e)] = int(dst)
+    return home
 
 
 def experts_per_device(E: int, ep: int) -> int:

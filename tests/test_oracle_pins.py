@@ -746,3 +746,134 @@ def test_plan_overflow_invariants(seed):
 def test_token_straggler_definition_and_paper_rows():
     assert orc.token_straggler([10, 20, 30, 40]) == 15.0
     assert orc.token_straggler([7, 7, 7]) == 0.0
+
+
+# ---------------------------------------------------------------- macro level: placement from history
+def test_history_update_fixed_point_average():
+    n = np.array([0, 1, 7, 1000, 123456], dtype=np.int64)
+    one = 1 << orc.HIST_FRAC_BITS
+    # shift 0 keeps the last batch only, whatever the history was
+    assert np.array_equal(orc.history_update(np.array([5, 0, 99, 1, 7]) * one, n, 0), n * one)
+    # a constant count is a fixed point, approached monotonically from below and from above
+    for start in (np.zeros(5, dtype=np.int64), 4 * n * one + 3):
+        h = start.copy()
+        for m in range(1, 200):
+            h2 = orc.history_update(h, n, 3)
+            assert np.all(np.abs(h2 - n * one) <= np.abs(h - n * one))
+            h = h2
+        assert np.all(np.abs(h - n * one) <= (1 << 3))            # within the flooring of the last steps
+    assert np.array_equal(orc.history_update(n * one, n, 5), n * one)
+    # against the real-valued recurrence h <- (1 - a) h + a n with a = 2^-shift: flooring loses < 1 unit per step
+    rng = np.random.default_rng(0)
+    h = np.zeros(5, dtype=np.int64)
+    ref = np.zeros(5)
+    for m in range(1, 40):
+        c = rng.integers(0, 5000, size=5)
+        h = orc.history_update(h, c, 2)
+        ref = 0.75 * ref + 0.25 * (c * one)
+        assert np.all(np.abs(h - ref) <= m)
+    # the floor is towards minus infinity for a falling history too
+    assert orc.history_update(np.array([10]), np.array([0]), 2)[0] == 10 + (-10 // 4) == 7
+
+
+@pytest.mark.parametrize("name", ["place_lpt_graham_example.txt", "place_lpt_capacity_example.txt"])
+def test_place_lpt_hand_worked(name):
+    g = read_golden(name)
+    owner, before, after, migrated = orc.place_lpt(g["P"][0], g["hist"], g["cap"][0], g["owner_in"])
+    assert owner.tolist() == g["owner_out"]
+    assert before.tolist() == g["load_before"] and after.tolist() == g["load_after"]
+    assert migrated == g["migrated"][0]
+    if "optimum" in g:
+        m = g["P"][0]
+        assert max(after) * 3 * m <= (4 * m - 1) * g["optimum"][0]           # Graham's bound, met with equality here
+        assert max(after) * 3 * m == (4 * m - 1) * g["optimum"][0]
+
+
+def best_makespan(P, hist, cap):
+    """Exhaustive search over all maps with at most cap experts per rank."""
+    best = None
+    for assign in itertools.product(range(P), repeat=len(hist)):
+        if max(np.bincount(assign, minlength=P)) > cap:
+            continue
+        load = np.bincount(assign, weights=hist, minlength=P).max()
+        best = load if best is None else min(best, load)
+    return best
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_place_lpt_against_exhaustive_search(seed):
+    rng = np.random.default_rng(seed)
+    P = int(rng.integers(2, 4))
+    E = int(rng.integers(P, 8))
+    hist = rng.integers(1, 50, size=E).astype(np.int64)
+    everything_on_zero = np.zeros(E, dtype=np.int32)
+    # without a binding limit this is Graham's list scheduling in LPT order: within 4/3 - 1/(3P) of the optimum
+    owner, before, after, _ = orc.place_lpt(P, hist, E, everything_on_zero)
+    opt = best_makespan(P, hist, E)
+    assert opt <= after.max() and after.max() * 3 * P <= (4 * P - 1) * opt
+    # with the limit: a valid map that is never worse than the one it replaces and never better than the optimum
+    cap = -(-E // P)
+    owner, before, after, migrated = orc.place_lpt(P, hist, cap, everything_on_zero)
+    assert np.bincount(owner, minlength=P).max() <= cap
+    assert best_makespan(P, hist, cap) <= after.max() <= before.max()
+    assert after.sum() == before.sum() == hist.sum()
+    assert migrated == int((owner != everything_on_zero).sum())
+    # placing again changes nothing: the same bins cannot be strictly better than themselves
+    again, b2, a2, m2 = orc.place_lpt(P, hist, cap, owner)
+    assert np.array_equal(again, owner) and m2 == 0 and np.array_equal(b2, after) and np.array_equal(a2, after)
+
+
+def test_place_lpt_keeps_what_it_cannot_improve_and_names_bins_after_ranks():
+    # any map with two experts per rank pairs the 10 with a 3: 13 cannot be lowered, the map stays
+    owner, before, after, migrated = orc.place_lpt(2, [10, 3, 3, 3], 2, [0, 0, 1, 1])
+    assert owner.tolist() == [0, 0, 1, 1] and migrated == 0 and after.tolist() == before.tolist() == [13, 6]
+    # a map that already equals the LPT bins up to the ranks' names costs no migration once it is improved on:
+    # start from the bins shifted by one rank with one expert misplaced
+    rng = np.random.default_rng(5)
+    P, per = 4, 4
+    hist = rng.choice(np.arange(1, 10000), size=P * per, replace=False).astype(np.int64)    # distinct
+    base, _, base_load, _ = orc.place_lpt(P, hist, per, np.zeros(P * per, dtype=np.int32))
+    shifted = (base + 1) % P
+    heavy_rank = int(np.argmax(orc.rank_loads(P, shifted, hist)))
+    light_rank = int(np.argmin(orc.rank_loads(P, shifted, hist)))
+    worse = shifted.copy()
+    a = [e for e in range(P * per) if shifted[e] == heavy_rank]
+    b = [e for e in range(P * per) if shifted[e] == light_rank]
+    ea, eb = min(a, key=lambda e: hist[e]), max(b, key=lambda e: hist[e])
+    assert heavy_rank != light_rank and hist[eb] > hist[ea]
+    worse[ea], worse[eb] = light_rank, heavy_rank                                   # heavier heavy rank
+    owner, before, after, migrated = orc.place_lpt(P, hist, per, worse)
+    assert before.max() > base_load.max() and sorted(after.tolist()) == sorted(base_load.tolist())
+    assert np.array_equal(owner, shifted) and migrated == 2                         # the two swapped experts go back
+    # relabelling the experts (distinct histories) permutes the map and leaves the loads alone
+    perm = rng.permutation(P * per)
+    o2, _, a2, _ = orc.place_lpt(P, hist[perm], per, np.zeros(P * per, dtype=np.int32))
+    assert sorted(a2.tolist()) == sorted(base_load.tolist())
+    with pytest.raises(ValueError):
+        orc.place_lpt(2, [1, 2, 3], 1, [0, 0, 1])
+
+
+def test_mark_dynamic_takes_each_ranks_busiest_experts():
+    owner = np.array([0, 0, 0, 1, 1, 1, 2, 2], dtype=np.int32)
+    hist = np.array([5, 9, 9, 1, 0, 7, 3, 3], dtype=np.int64)
+    assert orc.mark_dynamic(3, owner, hist, 2).tolist() == [0, 1, 1, 1, 0, 1, 1, 1]     # ties: lowest id first
+    assert orc.mark_dynamic(3, owner, hist, 1).tolist() == [0, 1, 0, 0, 0, 1, 1, 0]
+    assert orc.mark_dynamic(3, owner, hist, 0).sum() == 0 and orc.mark_dynamic(3, owner, hist, 5).sum() == 8
+    # on the contiguous map with history = popularity it is the workload generator's own choice
+    import workloads
+    wl = workloads.make("C4", T=64, d=8, f=8)
+    pop = np.round(np.exp(wl.bias) * 1e6).astype(np.int64)
+    assert np.array_equal(orc.mark_dynamic(wl.P, wl.owner(), pop, 4), wl.dyn_flags(4))
+
+
+def test_apply_moves_gives_the_planned_loads():
+    rng = np.random.default_rng(3)
+    P, E = 4, 16
+    owner = (np.arange(E) // 4).astype(np.int32)
+    n = rng.integers(0, 500, size=E).astype(np.int64)
+    flags = np.ones(E, dtype=np.uint8)
+    moves, before, after = orc.plan_whole(P, owner, n, flags, np.full(P, 2), 0)
+    assert moves
+    home = orc.apply_moves(owner, moves)
+    assert np.array_equal(orc.rank_loads(P, home, n), after)
+    assert np.array_equal(orc.apply_moves(owner, []), owner)
