@@ -376,6 +376,49 @@ int32_t feplb_plan(int32_t P, int32_t E, const int32_t* owner, const int64_t* n,
                    int64_t* load_before, int64_t* load_after,
                    int32_t* chosen_rank);
 
+/* ------------------------------------------------------------------ macro level: placement from history (host only)
+ * Section 2.3 (and the system figure): beside the per-micro-batch balancer, a Router Predictor
+ * re-assigns experts to devices now and then from routing history, at checkpoint time so that
+ * the migration cost is spread out.  The paper gives no algorithm; this build's rule:
+ *
+ * feplb_history_update keeps an exponential moving average of the per-expert counts in fixed
+ * point (FEPLB_HIST_FRAC_BITS fractional bits, so every rank derives the same integers):
+ *     hist[e] += floor(((n[e] << 16) - hist[e]) / 2^shift)     decay 1 - 2^-shift per call
+ * (shift = 0 keeps the last batch only).  0 <= shift <= 30, 0 <= n[e] < 2^46.
+ *
+ * feplb_place derives a new expert -> rank map: longest processing time first -- experts by
+ * history, largest first (lowest id on ties), each to the bin with the least accumulated
+ * history among the bins that hold fewer than `cap` experts (lowest bin on ties).  The new map
+ * is taken only if its largest bin is strictly below the largest rank load of owner_in under
+ * the same history (otherwise owner_out = owner_in and *n_migrated = 0).  Bins are named after
+ * ranks so that many experts stay: the (bin, rank) pair sharing the most experts first (lowest
+ * bin, then lowest rank on ties).  Needs cap * P >= E.  load_before / load_after [P] are the
+ * predicted rank loads under owner_in / owner_out (may be NULL); *n_migrated counts experts
+ * whose rank changes (may be NULL).
+ *
+ * feplb_mark_dynamic flags on every rank its `dyn` experts with the largest history (lowest id
+ * on ties) as the dynamic ones (Section 2.3 gives only their number).
+ * All pointers are host memory.
+ */
+#define FEPLB_HIST_FRAC_BITS 16
+
+int32_t feplb_history_update(int32_t E, int64_t* hist, const int64_t* n, int32_t shift);
+int32_t feplb_place(int32_t P, int32_t E, const int64_t* hist, int32_t cap, const int32_t* owner_in,
+                    int32_t* owner_out, int64_t* load_before, int64_t* load_after,
+                    int32_t* n_migrated);
+int32_t feplb_mark_dynamic(int32_t P, int32_t E, const int32_t* owner, const int64_t* hist,
+                           int32_t dyn, uint8_t* dyn_flag);
+
+/* ------------------------------------------------------------------ straggler bookkeeping (host only)
+ * Section 3.1, Metrics: the straggler of a per-rank quantity (tokens, or grouped-GEMM time) is
+ * its maximum over the ranks minus its mean.  feplb_apply_moves gives the rank on which each
+ * expert runs once a plan's whole-expert moves are applied (home[e] = owner[e] unless a move
+ * names e, then its dst).
+ */
+int32_t feplb_apply_moves(int32_t P, int32_t E, const int32_t* owner, const feplb_move* moves,
+                          int32_t n_moves, int32_t* home);
+int32_t feplb_straggler(int32_t P, const double* per_rank, double* straggler);
+
 #ifdef __cplusplus
 }
 #endif

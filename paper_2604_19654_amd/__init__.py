@@ -10,5 +10,6 @@ from .binding import (  # noqa: F401
     BWD_SCHEDULE, BWD_TRANSPOSE, BWD_DGRAD, BWD_WGRAD, BWD_ALL, BWD_ACCUMULATE,
     feplb_grouped_ffn_backward, feplb_grouped_ffn_backward_wt_bytes,
     feplb_combine_backward, feplb_route_topk_backward,
+    feplb_history_update, feplb_place, feplb_mark_dynamic, feplb_apply_moves, feplb_straggler, HIST_FRAC_BITS,
 )
 from .layer import RankLayer, LayerBuffers  # noqa: F401

@@ -82,6 +82,13 @@ def lib():
         L.feplb_expert_bytes.restype = sz
         L.feplb_plan.argtypes = [i32, i32, vp, vp, vp, vp, i64, i32, i32, C.POINTER(Move), i32,
                                  C.POINTER(i32), vp, vp, C.POINTER(i32)]
+        L.feplb_history_update.argtypes = [i32, vp, vp, i32]
+        L.feplb_place.argtypes = [i32, i32, vp, i32, vp, vp, vp, vp, C.POINTER(i32)]
+        L.feplb_mark_dynamic.argtypes = [i32, i32, vp, vp, i32, vp]
+        L.feplb_apply_moves.argtypes = [i32, i32, vp, C.POINTER(Move), i32, vp]
+        L.feplb_straggler.argtypes = [i32, vp, C.POINTER(C.c_double)]
+        for name in ("feplb_history_update", "feplb_place", "feplb_mark_dynamic", "feplb_apply_moves", "feplb_straggler"):
+            getattr(L, name).restype = i32
         for name in ("feplb_route_topk", "feplb_permute", "feplb_permute_append", "feplb_grouped_ffn", "feplb_grouped_ffn_static", "feplb_grouped_ffn_train",
                      "feplb_grouped_ffn_backward", "feplb_unpermute_combine", "feplb_combine_backward",
                      "feplb_route_topk_backward",
@@ -402,3 +409,66 @@ def feplb_plan(P, owner, n, dyn_flag, slots, tau=0, mode=PLAN_WHOLE, this_rank=-
            "feplb_plan")
     out = [(m.expert, m.src, m.dst, int(m.rows), int(m.ord_lo)) for m in moves[: n_moves.value]]
     return out, before, after, chosen.value
+
+
+HIST_FRAC_BITS = 16   # FEPLB_HIST_FRAC_BITS
+
+
+def feplb_history_update(hist: np.ndarray, n, shift: int) -> np.ndarray:
+    """Host-only.  Updates the int64 history array in place (and returns it)."""
+    if hist.dtype != np.int64 or not hist.flags.c_contiguous:
+        raise FeplbError("feplb_history_update: hist must be a contiguous int64 array")
+    n = np.ascontiguousarray(n, dtype=np.int64)
+    if n.shape != hist.shape:
+        raise FeplbError("feplb_history_update: hist and n differ in length")
+    _check(lib().feplb_history_update(int(hist.shape[0]), hist.ctypes.data, n.ctypes.data, int(shift)),
+           "feplb_history_update")
+    return hist
+
+
+def feplb_place(P, hist, cap, owner_in):
+    """Host-only.  Returns (owner_out int32 [E], load_before, load_after, migrated)."""
+    hist = np.ascontiguousarray(hist, dtype=np.int64)
+    owner_in = np.ascontiguousarray(owner_in, dtype=np.int32)
+    E = int(hist.shape[0])
+    if owner_in.shape[0] != E:
+        raise FeplbError("feplb_place: array lengths differ")
+    owner_out = np.zeros(E, dtype=np.int32)
+    before = np.zeros(P, dtype=np.int64)
+    after = np.zeros(P, dtype=np.int64)
+    moved = C.c_int32(0)
+    _check(lib().feplb_place(P, E, hist.ctypes.data, int(cap), owner_in.ctypes.data, owner_out.ctypes.data,
+                             before.ctypes.data, after.ctypes.data, C.byref(moved)), "feplb_place")
+    return owner_out, before, after, int(moved.value)
+
+
+def feplb_mark_dynamic(P, owner, hist, dyn) -> np.ndarray:
+    """Host-only.  -> uint8 [E] flags."""
+    owner = np.ascontiguousarray(owner, dtype=np.int32)
+    hist = np.ascontiguousarray(hist, dtype=np.int64)
+    flag = np.zeros(owner.shape[0], dtype=np.uint8)
+    if hist.shape != owner.shape:
+        raise FeplbError("feplb_mark_dynamic: array lengths differ")
+    _check(lib().feplb_mark_dynamic(P, int(owner.shape[0]), owner.ctypes.data, hist.ctypes.data, int(dyn),
+                                    flag.ctypes.data), "feplb_mark_dynamic")
+    return flag
+
+
+def feplb_apply_moves(P, owner, moves) -> np.ndarray:
+    """Host-only.  moves as returned by feplb_plan.  -> int32 [E]: the rank that runs each expert."""
+    owner = np.ascontiguousarray(owner, dtype=np.int32)
+    arr = (Move * max(len(moves), 1))()
+    for i, (e, src, dst, rows, lo) in enumerate(moves):
+        arr[i] = Move(int(e), int(src), int(dst), 0, int(rows), int(lo))
+    home = np.zeros(owner.shape[0], dtype=np.int32)
+    _check(lib().feplb_apply_moves(P, int(owner.shape[0]), owner.ctypes.data, arr, len(moves), home.ctypes.data),
+           "feplb_apply_moves")
+    return home
+
+
+def feplb_straggler(values) -> float:
+    """Host-only.  max - mean of a per-rank quantity."""
+    v = np.ascontiguousarray(values, dtype=np.float64)
+    out = C.c_double(0.0)
+    _check(lib().feplb_straggler(int(v.shape[0]), v.ctypes.data, C.byref(out)), "feplb_straggler")
+    return float(out.value)

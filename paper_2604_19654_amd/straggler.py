@@ -15,7 +15,12 @@ are library calls.  Inputs are synthetic (Zipf-biased logits, one popularity
 permutation per micro-batch): the paper's traces are not public, so the figures show
 the mechanism, not the paper's numbers.
 
+With --predictor the study covers the macro level of Section 2.3 instead: the popularity
+persists over the micro-batches, the library keeps a routing history, derives a new
+expert -> rank map from it and the same metrics are reported with and without that map.
+
     python -m paper_2604_19654_amd.straggler --ep 2 4 8 --dyn 2 4 8 --batches 8
+    python -m paper_2604_19654_amd.straggler --predictor --ep 2 4 8 --batches 6 --warm 4
 """
 from __future__ import annotations
 
@@ -32,9 +37,8 @@ from . import binding as B
 
 
 def straggler(values) -> float:
-    """max - mean (Section 3.1 Metrics)."""
-    v = np.asarray(values, dtype=np.float64)
-    return float(v.max() - v.mean())
+    """max - mean over the ranks (Section 3.1 Metrics), by the library."""
+    return B.feplb_straggler(values)
 
 
 def plan_counts(P: int, owner, counts, dyn_flag, dyn: int, tau: int = 0):
@@ -45,15 +49,13 @@ def plan_counts(P: int, owner, counts, dyn_flag, dyn: int, tau: int = 0):
 
 
 def placement(P: int, owner, counts, moves) -> List[List[int]]:
-    """Row counts of the groups every rank runs: its own experts that stay, then the experts
-    it receives.  Experts without rows form no group."""
-    home = {int(e): int(owner[e]) for e in range(len(owner))}
-    for (e, _src, dst, _rows, _lo) in moves:
-        home[int(e)] = int(dst)
+    """Row counts of the groups every rank runs, in expert order, with the plan's moves applied
+    by the library.  Experts without rows form no group."""
+    home = B.feplb_apply_moves(P, owner, moves)
     groups: List[List[int]] = [[] for _ in range(P)]
     for e in range(len(owner)):
         if counts[e] > 0:
-            groups[home[e]].append(int(counts[e]))
+            groups[int(home[e])].append(int(counts[e]))
     return groups
 
 
@@ -124,7 +126,7 @@ class FfnTimer:
 def study(P: int, dyn_list: Sequence[int], n_batches: int, tokens_per_rank: int = 16384, E: int = 128,
           k: int = 8, d: int = 6144, f: int = 2048, tau: int = 0, seed0: int = 5000, gemm_dyn: int = 4,
           device="cuda:0", with_gemm: bool = True, with_backward: bool = False,
-          tau_list: Sequence[int] = ()) -> Dict:
+          tau_list: Sequence[int] = (), keep_records: bool = False) -> Dict:
     """Mean token straggler before / after the plan for every dyn in dyn_list, and (for
     dyn = gemm_dyn) the mean GEMM straggler before / after, over n_batches micro-batches."""
     T = P * tokens_per_rank
@@ -132,6 +134,7 @@ def study(P: int, dyn_list: Sequence[int], n_batches: int, tokens_per_rank: int 
     by_tau = {int(t): [] for t in tau_list}        # token straggler after the plan, dyn = gemm_dyn
     gemm = {"before": [], "after": []}
     layer = {"fwd_before": [], "bwd_before": [], "fwd_after": [], "bwd_after": []}
+    records = []                                   # per micro-batch: what the figures were computed from
     timer = None
     for b in range(n_batches):
         # token rows are not needed: the smallest legal widths keep the generator cheap
@@ -140,6 +143,8 @@ def study(P: int, dyn_list: Sequence[int], n_batches: int, tokens_per_rank: int 
         torch.cuda.synchronize()
         counts = counts_dev.cpu().numpy().astype(np.int64)
         owner = wl.owner()
+        rec = {"seed": seed0 + b, "counts": counts, "loads": {}, "token_straggler": {}}
+        records.append(rec)
         for t in by_tau:
             by_tau[t].append(straggler(plan_counts(P, owner, counts, wl.dyn_flags(gemm_dyn), gemm_dyn, t)[2]))
         first = True
@@ -147,8 +152,10 @@ def study(P: int, dyn_list: Sequence[int], n_batches: int, tokens_per_rank: int 
             moves, before, after = plan_counts(P, owner, counts, wl.dyn_flags(n), n, tau)
             if first:
                 tok["before"].append(straggler(before))
+                rec["loads"]["before"], rec["token_straggler"]["before"] = before, tok["before"][-1]
                 first = False
             tok[f"dyn{n}"].append(straggler(after))
+            rec["loads"][f"dyn{n}"], rec["token_straggler"][f"dyn{n}"] = after, tok[f"dyn{n}"][-1]
             if with_gemm and n == gemm_dyn:
                 shares_before = placement(P, owner, counts, [])
                 shares_after = placement(P, owner, counts, moves)
@@ -174,6 +181,70 @@ def study(P: int, dyn_list: Sequence[int], n_batches: int, tokens_per_rank: int 
         out["gemm_reduction_pct"] = 100.0 * (1.0 - ga / gb) if gb > 0 else 0.0
     if layer["fwd_before"]:
         out["slowest_rank_ffn_ms"] = {key: float(np.mean(v)) for key, v in layer.items()}
+    if keep_records:
+        out["records"] = records
+    return out
+
+
+def predictor_study(P: int, dyn: int, n_batches: int, warm: int, shift: int = 2, tokens_per_rank: int = 16384,
+                    E: int = 128, k: int = 8, d: int = 6144, f: int = 2048, tau: int = 0, seed0: int = 7000,
+                    device="cuda:0", with_gemm: bool = True, keep_records: bool = False) -> Dict:
+    """Macro level of Section 2.3 on synthetic routing whose popularity persists over the micro-batches
+    of a run (one popularity seed, new logit noise per batch).  The first `warm` batches only feed the
+    library's routing history; then the library derives a new expert -> rank map from it
+    (feplb_place) and marks each rank's `dyn` busiest experts as dynamic (feplb_mark_dynamic).  On the
+    remaining batches the token straggler (and, from the per-rank FFN times, the GEMM straggler) is
+    reported for four set-ups: the contiguous map, the contiguous map with the per-micro-batch plan,
+    the placed map, the placed map with the plan.  Sequencing only: routing, history, placement,
+    plan and FFN are library calls."""
+    T = P * tokens_per_rank
+    per = E // P
+    hist = np.zeros(E, dtype=np.int64)
+    owner0 = None
+    placed = None
+    keys = ("contiguous", "contiguous+plan", "placed", "placed+plan")
+    tok = {key: [] for key in keys}
+    gemm = {key: [] for key in keys}
+    records = []
+    timer = None
+    slots = np.full(P, dyn, dtype=np.int32)
+    for b in range(n_batches):
+        wl = workloads.make("C4", device=device, seed=seed0 + b, pop_seed=seed0, P=P, T=T, d=8, f=8, E=E, k=k)
+        _ids, _w, counts_dev = B.feplb_route_topk(wl.logits, k)
+        torch.cuda.synchronize()
+        counts = counts_dev.cpu().numpy().astype(np.int64)
+        if owner0 is None:
+            owner0 = wl.owner()
+        if b < warm:
+            B.feplb_history_update(hist, counts, shift if b else 0)     # the first batch starts the history
+            continue
+        if placed is None:
+            owner1, load_before, load_after, migrated = B.feplb_place(P, hist, per, owner0)
+            placed = dict(owner=owner1, predicted_before=load_before, predicted_after=load_after, migrated=migrated,
+                          hist=hist.copy())
+        rec = {"seed": seed0 + b, "counts": counts, "loads": {}, "token_straggler": {}}
+        records.append(rec)
+        for name, owner in (("contiguous", owner0), ("placed", placed["owner"])):
+            flags = B.feplb_mark_dynamic(P, owner, hist, dyn)
+            moves, before, after, _ = B.feplb_plan(P, owner, counts, flags, slots, tau, B.PLAN_WHOLE)
+            for key, loads, mv in ((name, before, []), (name + "+plan", after, moves)):
+                tok[key].append(straggler(loads))
+                rec["loads"][key], rec["token_straggler"][key] = loads, tok[key][-1]
+                if with_gemm:
+                    if timer is None:
+                        timer = FfnTimer(d, f, max_rows=int(counts.sum()), max_groups=min(E, B.MAX_GROUPS), device=device)
+                    gemm[key].append(straggler([timer.time_ms(s) for s in placement(P, owner, counts, mv)]))
+        B.feplb_history_update(hist, counts, shift)
+    out = {"P": P, "dyn": dyn, "batches": n_batches, "warm": warm, "shift": shift, "tokens_per_rank": tokens_per_rank,
+           "E": E, "k": k, "migrated_experts": placed["migrated"],
+           "predicted_max_load_rows": {"contiguous": float(placed["predicted_before"].max()) / (1 << B.HIST_FRAC_BITS),
+                                       "placed": float(placed["predicted_after"].max()) / (1 << B.HIST_FRAC_BITS)},
+           "token_straggler": {key: float(np.mean(v)) for key, v in tok.items()}}
+    if with_gemm:
+        out["gemm_straggler_ms"] = {key: float(np.mean(v)) for key, v in gemm.items()}
+    if keep_records:
+        out["records"] = records
+        out["placed"] = placed
     return out
 
 
@@ -191,8 +262,27 @@ def main():
     ap.add_argument("--no-gemm", action="store_true")
     ap.add_argument("--backward", action="store_true",
                     help="also time every rank's FFN training step (forward keeping the SwiGLU derivatives, backward) and report the slowest rank's times before and after the plan")
+    ap.add_argument("--predictor", action="store_true",
+                    help="macro level: routing whose popularity persists over the micro-batches; history -> placement, "
+                         "then the four set-ups (contiguous / placed map, without / with the per-micro-batch plan)")
+    ap.add_argument("--warm", type=int, default=4, help="micro-batches that only feed the history (--predictor)")
     a = ap.parse_args()
     B.lib()
+    if a.predictor:
+        rows = []
+        for P in a.ep:
+            r = predictor_study(P, 4, a.batches + a.warm, a.warm, tokens_per_rank=a.tokens_per_rank, d=a.d, f=a.f, tau=a.tau,
+                                with_gemm=not a.no_gemm)
+            rows.append(r)
+            print(json.dumps(r), flush=True)
+        print("\n| EP | experts migrated | token straggler: contiguous | + plan | placed | placed + plan | GEMM straggler (ms): contiguous | + plan | placed | placed + plan |")
+        print("|---|---|---|---|---|---|---|---|---|---|")
+        for r in rows:
+            t, g = r["token_straggler"], r.get("gemm_straggler_ms")
+            keys = ("contiguous", "contiguous+plan", "placed", "placed+plan")
+            print(f"| {r['P']} | {r['migrated_experts']} | " + " | ".join(f"{t[key]:.0f}" for key in keys) + " | " +
+                  " | ".join(f"{g[key]:.3f}" if g else "-" for key in keys) + " |")
+        return
     rows = []
     for P in a.ep:
         r = study(P, a.dyn, a.batches, a.tokens_per_rank, d=a.d, f=a.f, tau=a.tau, with_gemm=not a.no_gemm, with_backward=a.backward,

@@ -214,3 +214,68 @@ def test_plan_latency_fits_the_papers_budget():
     med = float(np.median(times)) * 1e6
     print(f"feplb_plan, E=128, EP=8, {n_moves.value} moves: median {med:.1f} us (ctypes call included)")
     assert med < 50.0
+
+
+# ---------------------------------------------------------------- macro level: placement from history
+@pytest.mark.parametrize("name", ["place_lpt_graham_example.txt", "place_lpt_capacity_example.txt"])
+def test_place_golden(name):
+    g = read_golden(name)
+    owner, before, after, migrated = fe.feplb_place(g["P"][0], g["hist"], g["cap"][0], g["owner_in"])
+    assert owner.tolist() == g["owner_out"] and migrated == g["migrated"][0]
+    assert before.tolist() == g["load_before"] and after.tolist() == g["load_after"]
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_predictor_matches_oracle_bit_for_bit(seed):
+    rng = np.random.default_rng(7000 + seed)
+    P, per = int(rng.integers(1, 9)), int(rng.integers(1, 33))
+    E = P * per
+    hist_o = np.zeros(E, dtype=np.int64)
+    hist_l = np.zeros(E, dtype=np.int64)
+    pop = rng.dirichlet(np.full(E, 0.3))
+    shift = int(rng.integers(0, 6))
+    for _ in range(6):
+        n = rng.multinomial(int(rng.integers(0, 200000)), pop).astype(np.int64)
+        hist_o = orc.history_update(hist_o, n, shift)
+        assert fe.feplb_history_update(hist_l, n, shift) is hist_l
+        assert np.array_equal(hist_l, hist_o)
+    if seed % 4 == 0:
+        hist_o[rng.integers(0, E, size=E // 2 + 1)] = hist_o[0]          # ties
+    owner_in = rng.permutation(np.arange(E) // per).astype(np.int32) if seed % 2 else (np.arange(E) // per).astype(np.int32)
+    cap = per + int(rng.integers(0, 3))
+    o_o, b_o, a_o, m_o = orc.place_lpt(P, hist_o, cap, owner_in)
+    o_l, b_l, a_l, m_l = fe.feplb_place(P, hist_o, cap, owner_in)
+    assert np.array_equal(o_l, o_o) and np.array_equal(b_l, b_o) and np.array_equal(a_l, a_o) and m_l == m_o
+    again = fe.feplb_place(P, hist_o, cap, o_l)
+    assert np.array_equal(again[0], o_l) and again[3] == 0              # placing again changes nothing
+    dyn = int(rng.integers(0, per + 2))
+    assert np.array_equal(fe.feplb_mark_dynamic(P, o_l, hist_o, dyn), orc.mark_dynamic(P, o_l, hist_o, dyn))
+    # straggler bookkeeping: where each expert runs after a whole-expert plan, and the metric
+    flags = fe.feplb_mark_dynamic(P, o_l, hist_o, max(dyn, 1))
+    n = rng.multinomial(50000, pop).astype(np.int64)
+    moves, before, after, _ = fe.feplb_plan(P, o_l, n, flags, np.full(P, 4, dtype=np.int32), 0, fe.PLAN_WHOLE)
+    home = fe.feplb_apply_moves(P, o_l, moves)
+    assert np.array_equal(home, orc.apply_moves(o_l, moves))
+    assert np.array_equal(orc.rank_loads(P, home, n), after)
+    assert fe.feplb_straggler(after) == orc.token_straggler(after)
+    assert fe.feplb_straggler(before) == orc.token_straggler(before)
+
+
+def test_history_floor_and_predictor_error_codes():
+    h = np.array([10, 7, 0], dtype=np.int64)
+    fe.feplb_history_update(h, [0, 0, 0], 2)
+    assert h.tolist() == [7, 5, 0]                                     # floor towards minus infinity: 10 + floor(-10/4)
+    with pytest.raises(fe.FeplbError):
+        fe.feplb_history_update(h, [0, 0, 0], 31)
+    with pytest.raises(fe.FeplbError):
+        fe.feplb_history_update(h, [0, -1, 0], 1)
+    with pytest.raises(fe.FeplbError, match="cannot hold"):
+        fe.feplb_place(2, [1, 2, 3], 1, [0, 0, 1])
+    with pytest.raises(fe.FeplbError):
+        fe.feplb_place(2, [1, 2, 3], 2, [0, 0, 2])                     # owner out of range
+    with pytest.raises(fe.FeplbError):
+        fe.feplb_apply_moves(2, [0, 1], [(5, 0, 1, 1, 0)])             # move names an expert that does not exist
+    assert fe.feplb_place(3, [], 0, [])[3] == 0
+    assert fe.feplb_straggler([3.0]) == 0.0
+    L = fe.lib()
+    assert L.feplb_straggler(0, None, None) == -1

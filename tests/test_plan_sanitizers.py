@@ -1,5 +1,5 @@
-"""The host-side plan (csrc/plan.cpp) built with AddressSanitizer and UndefinedBehaviorSanitizer and
-driven over two thousand random cases in both modes: any out-of-bounds access, signed overflow or
+"""The host-side plan, placement and bookkeeping (csrc/plan.cpp) built with AddressSanitizer and
+UndefinedBehaviorSanitizer and driven over two thousand random cases, the plan in both modes: any out-of-bounds access, signed overflow or
 other undefined behaviour aborts the run.  Host code only; no GPU, no HIP call."""
 import os
 import shutil
@@ -39,6 +39,28 @@ int main() {
     int32_t rc = feplb_plan(P, E, owner.data(), n.data(), dyn.data(), slots.data(), 0, 0, -1, moves.data(), 0, &nm,
                             before.data(), after.data(), &chosen);
     if (rc != 0 && rc != FEPLB_ECAPACITY) { std::printf("rc %d with an empty move table\n", rc); return 3; }
+    // macro level: history, placement (random current map, limit with and without slack), marking, bookkeeping
+    std::vector<int64_t> hist(E, 0);
+    for (int u = 0; u < 3; ++u) {
+      for (int e = 0; e < E; ++e) n[e] = rnd(4) ? (int64_t)rnd(200000) : 0;
+      if (feplb_history_update(E, hist.data(), n.data(), (int32_t)rnd(8)) != 0) return 4;
+    }
+    std::vector<int32_t> cur(E), out(E), home(E);
+    for (int e = 0; e < E; ++e) cur[e] = (int32_t)rnd(P);
+    int32_t moved = -1;
+    if (feplb_place(P, E, hist.data(), per + (int32_t)rnd(3), cur.data(), out.data(), before.data(), after.data(), &moved) != 0) return 5;
+    int64_t a2 = 0, b2 = 0;
+    for (int r = 0; r < P; ++r) { a2 += after[r]; b2 += before[r]; }
+    if (a2 != b2 || moved < 0 || moved > E) { std::printf("bad placement in case %d\n", it); return 6; }
+    if (feplb_place(P, E, hist.data(), per - 1, cur.data(), out.data(), nullptr, nullptr, nullptr) != FEPLB_ESHAPE) return 7;
+    if (feplb_mark_dynamic(P, E, out.data(), hist.data(), (int32_t)rnd(per + 2), dyn.data()) != 0) return 8;
+    if (feplb_plan(P, E, out.data(), n.data(), dyn.data(), slots.data(), 0, 0, -1, moves.data(), (int32_t)moves.size(), &nm,
+                   before.data(), after.data(), &chosen) != 0) return 9;
+    if (feplb_apply_moves(P, E, out.data(), moves.data(), nm, home.data()) != 0) return 10;
+    std::vector<double> v(P);
+    for (int r = 0; r < P; ++r) v[r] = (double)after[r];
+    double st = -1.0;
+    if (feplb_straggler(P, v.data(), &st) != 0 || st < 0.0) return 11;
   }
   std::puts("ok");
   return 0;

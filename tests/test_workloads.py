@@ -44,3 +44,15 @@ def test_dyn_flags_pick_four_per_rank():
     wl = workloads.make("C4", T=64, d=8, f=8)
     flag = wl.dyn_flags(4)
     assert flag.reshape(8, 16).sum(axis=1).tolist() == [4] * 8
+
+
+def test_popularity_seed_persists_over_micro_batches():
+    a = workloads.make("C4", T=256, d=8, f=8, seed=50, pop_seed=7)
+    b = workloads.make("C4", T=256, d=8, f=8, seed=51, pop_seed=7)
+    c = workloads.make("C4", T=256, d=8, f=8, seed=51)
+    assert np.array_equal(a.bias, b.bias) and not np.array_equal(a.logits.numpy(), b.logits.numpy())
+    assert not np.array_equal(b.bias, c.bias)
+    # the noise follows `seed` alone
+    assert np.allclose(b.logits.numpy() - b.bias.astype(np.float32), c.logits.numpy() - c.bias.astype(np.float32), atol=1e-4)
+    # without pop_seed nothing changes
+    assert np.array_equal(workloads.make("C3", T=64, d=8, f=8).bias, workloads.make("C3", T=64, d=8, f=8, pop_seed=1003).bias)

@@ -18,7 +18,9 @@ Draw order per workload, seed ``s = 1000 + c`` for workload ``Cc``:
 popularity (permutation or Dirichlet, NumPy, seed s) -> logit noise (torch,
 seed s) -> token rows X (torch, seed s + 1) -> expert e's weights (torch,
 seed ``(s + 2) * 4096 + e``, gate then up then down), drawn on demand so that
-only the experts a rank actually runs are ever materialised.
+only the experts a rank actually runs are ever materialised.  With ``pop_seed=``
+the popularity is drawn from that seed instead, so that a series of micro-batches
+(seeds s, s+1, ...) shares one popularity, as the batches of one training run do.
 """
 from __future__ import annotations
 
@@ -146,12 +148,15 @@ def make(name: str, device="cpu", **override) -> Workload:
         raise KeyError(name)
     p = dict(_SHAPES[name])
     seed = int(override.pop("seed", 1000 + int(name[1:])))
+    # the experts' popularity may keep its own seed while the logit noise, tokens and weights
+    # follow `seed`: micro-batches of one training run share a popularity and differ in the rest
+    pop_seed = int(override.pop("pop_seed", seed))
     p.update(override)
     T, d, f, E, k, P = (int(p[x]) for x in ("T", "d", "f", "E", "k", "P"))
     if E % P:
         raise ValueError("E must be a multiple of P")
     dev = torch.device(device)
-    rng = np.random.default_rng(seed)
+    rng = np.random.default_rng(pop_seed)
     per = E // P
 
     swapped = -1
