@@ -24,10 +24,14 @@ if ROOT not in sys.path:
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 (no sparsity)
 HBM_PEAK_GBPS = 8000.0           # MI355X HBM3E
-# HBM bytes per launch of the gate/up GEMM (read + written), measured with rocprofv3 --pmc
-# FETCH_SIZE / WRITE_SIZE and calibrated against the row-copy kernel of the same run; see
-# profiles/hbm_traffic_C4_pmc.md.  Only for the workload it was measured on.
-MEASURED_TRAFFIC_BYTES = {"C4": 5.103e9 + 0.268e9}
+# HBM bytes per launch (read, written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by what the
+# same counters read for the row-copy and combine kernels of the same run (sizes known); see the named profile.
+# The figures belong to the kernel source they were measured on: bench.py reports them only while
+# csrc/ffn.hip still has that content (sha256), and null otherwise.
+MEASURED_TRAFFIC = {
+    "C4": {"profile": "profiles/hbm_traffic_C4_pmc.md", "ffn_hip_sha256": "UNMEASURED",
+           "gate_up": {"read": 5.103e9, "written": 0.268e9}, "down": None},
+}
 METRIC = "grouped-FFN TFLOP/s & % bf16 MFMA peak per rank share; permute/combine GB/s"
 
 
@@ -35,7 +39,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def time_workload(name, steps, warmup, source_kind="device", fused_gather=True, yp_dtype="f32", early_static=False):
+def time_workload(name, steps, warmup, source_kind="device", fused_gather=True, yp_dtype="f32", early_static=True):
     import numpy as np
     import torch
     from paper_2604_19654_amd import runner
@@ -112,6 +116,21 @@ def time_workload(name, steps, warmup, source_kind="device", fused_gather=True, 
         res["graph_replay_ms_per_step"] = (time.perf_counter() - t0) * 1e3 / steps
         res["ffn_tflops_step_graph_replay"] = ffn_flops / (res["graph_replay_ms_per_step"] * 1e-3) / 1e12
         del graph
+    # per-group rows as the device has them (read back once, after the timed region): the algorithmic
+    # bytes of a launch count the weights of its NON-EMPTY groups only
+    G = len(p.groups)
+    offs = layer.buf.offsets[: G + 1].cpu().numpy().astype(np.int64)
+    rows_g = np.diff(offs)
+    ranges = [(0, len(p.static_weights)), (len(p.static_weights), G)] if n_up == 2 else [(0, G)]
+    launches = []
+    for (g0, g1) in ranges:
+        r_l, ne = int(rows_g[g0:g1].sum()), int((rows_g[g0:g1] > 0).sum())
+        launches.append({"groups": [g0, g1], "rows": r_l, "nonempty_groups": ne,
+                         "gate_up_bytes": ne * 2 * d * f * 2 + r_l * d * 2 + r_l * f * 2,
+                         "down_bytes": ne * d * f * 2 + r_l * f * 2 + r_l * d * yp_bytes})
+    res["group_rows"] = rows_g.tolist()
+    res["nonempty_groups"] = int((rows_g > 0).sum())
+    res["launches"] = launches
     res["fused_gather"] = fused_gather
     res["yp_dtype"] = yp_dtype
     # the permute step with its row gather (X -> Xp), timed on its own when the step's GEMM gathers the rows itself
@@ -130,18 +149,94 @@ def time_workload(name, steps, warmup, source_kind="device", fused_gather=True, 
     }
     if p.rebalanced:
         nbytes = sum(t.numel() * t.element_size() for t in p.remote_sources.values())
+        engine = ("blit kernel on the compute units (same-device copy: the stand-in for a peer GPU's memory; a peer copy over xGMI would use an SDMA engine)"
+                  if p.source_kind == "device" else "SDMA engine, pinned host memory over PCIe")
         if early_static:
             # the copies run beside the static GEMM (and, from device memory, as a blit kernel that
             # competes with it for compute units), so this is a span, not a copy rate
-            res["staging"] = dict(bytes=nbytes, source=p.source_kind, copy_span_ms=ms["copy"],
+            res["staging"] = dict(bytes=nbytes, source=p.source_kind, engine=engine, copy_span_ms=ms["copy"],
                                   wait_after_static_ms=ms["wait_for_copy"])
         else:
-            res["staging"] = dict(bytes=nbytes, source=p.source_kind, copy_ms=ms["copy"],
+            res["staging"] = dict(bytes=nbytes, source=p.source_kind, engine=engine, copy_ms=ms["copy"],
                                   copy_gbps=nbytes / (ms["copy"] * 1e-3) / 1e9,
                                   wait_after_static_ms=ms["wait_for_copy"])
         res["moves"] = p.moves
     res["pct_mfma_peak_ffn_kernels"] = 100.0 * res["ffn_tflops_kernels"] / MFMA_BF16_PEAK_TFLOPS
+    res["reference_copy_gbps"] = _reference_copy_gbps(layer.buf.Y)
+    res["rooflines"] = _rooflines(name, res)
     return p, res
+
+
+def _reference_copy_gbps(buf):
+    """What a plain device-to-device copy of the same size reaches on this machine (torch's elementwise
+    copy kernel, read + written bytes): the plateau of 1:1 read/write traffic, for context."""
+    import torch
+    from paper_2604_19654_amd import binding as B
+    dst = torch.empty_like(buf)
+    e0, e1 = B.HipEvent(), B.HipEvent()
+    dst.copy_(buf)
+    e0.record(None)
+    for _ in range(10):
+        dst.copy_(buf)
+    e1.record(None)
+    e1.synchronize()
+    return 2 * buf.numel() * buf.element_size() / (e0.elapsed_ms(e1) / 10 * 1e-3) / 1e9
+
+
+def _traffic(name, kernel):
+    """Measured HBM bytes per launch of `kernel` on workload `name`, or None when there is no
+    measurement for the kernel source as it stands."""
+    import hashlib
+    m = MEASURED_TRAFFIC.get(name)
+    if not m or not m.get(kernel):
+        return None
+    src = os.path.join(ROOT, "paper_2604_19654_amd", "csrc", "ffn.hip")
+    with open(src, "rb") as fh:
+        if hashlib.sha256(fh.read()).hexdigest() != m["ffn_hip_sha256"]:
+            return None
+    return m[kernel]["read"] + m[kernel]["written"]
+
+
+def _rooflines(name, res):
+    """One roofline object per kernel of the step: algorithmic flops or bytes per launch (no padding, no empty
+    groups) over the average launch duration measured with HIP events on the launch stream."""
+    d, f, R, T, k, E = res["d"], res["f"], res["R"], res["T"], res["k"], res["E"]
+    ms, n = res["ms"], res["gate_up_launches_per_step"]
+    L = res["launches"]
+    yp_bytes = 2 if res["yp_dtype"] == "bf16" else 4
+
+    def mfma(kernel, key, flops_per_row, bytes_key):
+        achieved = flops_per_row * R / (ms[key] * 1e-3) / 1e12
+        return {"kernel": kernel, "bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": _traffic(name, key),
+                "traffic_unit": "HBM bytes per launch, read + written (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE)",
+                "traffic_profile": MEASURED_TRAFFIC.get(name, {}).get("profile"),
+                "launches_per_step": n, "avg_launch_ms": ms[key] / n, "flops_per_launch": flops_per_row * R / n,
+                "algorithmic_bytes_per_launch": sum(l[bytes_key] for l in L) / n,
+                "per_launch": [{"rows": l["rows"], "nonempty_groups": l["nonempty_groups"], "algorithmic_bytes": l[bytes_key]} for l in L]}
+
+    def hbm(kernel, t_ms, nbytes, traffic=None):
+        achieved = nbytes / (t_ms * 1e-3) / 1e9
+        return {"kernel": kernel, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic, "avg_launch_ms": t_ms, "algorithmic_bytes_per_launch": nbytes}
+
+    out = {
+        "gate_up": mfma("grouped_gemm_kernel<0,true,false> (gate/up GEMM + SwiGLU)", "gate_up", 4.0 * d * f, "gate_up_bytes"),
+        "down": mfma("grouped_gemm_kernel<1,%s,false> (down GEMM)" % ("true" if yp_bytes == 2 else "false"), "down", 2.0 * d * f, "down_bytes"),
+        "combine": hbm("combine_kernel", ms["combine"], R * d * yp_bytes + T * d * 2 + T * k * 8),
+        "permute_with_gather": hbm("chunk_hist + chunk_scan + group_offsets + assign_rows + gather_rows_kernel",
+                                   res["permute_with_gather_ms"], 2 * R * d * 2 + T * k * 8 + R * 4),
+        "row_gather_alone": hbm("gather_rows_kernel (the step above minus its index kernels)",
+                                res["hbm_kernels"]["row_gather_alone"]["ms"], 2 * R * d * 2),
+        # the router is bound by its vector ALU work, not by the 67 MB it reads (T*E*4 + T*k*8 bytes): about 45 vector
+        # operations per logit (5 per entry of the sorted list of k = 8, plus the exponentials and the histogram),
+        # against 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3e12 lane operations per second
+        "route": {"kernel": "route_topk kernel", "bound": "alu", "achieved": 45.0 * T * E / (ms["route"] * 1e-3) / 1e12,
+                  "peak": 256 * 4 * 16 * 2.4e9 / 1e12, "unit": "T lane-op/s",
+                  "frac": 45.0 * T * E / (ms["route"] * 1e-3) / (256 * 4 * 16 * 2.4e9), "traffic": None,
+                  "avg_launch_ms": ms["route"], "hbm_gbps": res["route_gbps"], "hbm_frac": res["route_gbps"] / HBM_PEAK_GBPS},
+    }
+    return out
 
 
 def _permute_ms(p, steps, with_rows=True):
@@ -297,13 +392,15 @@ def main():
     ap.add_argument("--workload", default="C4")
     ap.add_argument("--source", default="device", choices=["device", "pinned"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--all", action="store_true", help="also time the other four workloads (reported under all_workloads)")
+    ap.add_argument("--all", action="store_true", help="also time the other four workloads (reported under other_workloads)")
+    ap.add_argument("--no-c3", action="store_true", help="skip the skewed share C3 that the default run times after the main workload")
     ap.add_argument("--cpu-tokens", type=int, default=65536)
     ap.add_argument("--no-training", action="store_true", help="skip the FFN training-step leg (forward keeping the SwiGLU derivatives, backward)")
     ap.add_argument("--yp-dtype", default="f32", choices=["f32", "bf16"],
                     help="type of the expert outputs Yp between the down GEMM and the combine")
-    ap.add_argument("--early-static", action="store_true",
-                    help="rebalanced share: launch the static experts before the host plan is known and append the replicas' groups behind the static FFN (default: plan first, one permute)")
+    ap.add_argument("--plan-first", dest="early_static", action="store_false",
+                    help="rebalanced share: read the counts back and plan before anything else is launched, one permute over all groups "
+                         "(default: the timeline of Section 2.3 -- static experts launched before the plan is known, replicas' groups appended behind the static FFN)")
     ap.add_argument("--materialize-xp", action="store_true",
                     help="permute writes the permuted copy Xp and the gate/up GEMM reads it (default: the GEMM gathers the rows itself)")
     a = ap.parse_args()
@@ -337,47 +434,54 @@ def main():
                 continue
             q, r = time_workload(name, a.steps, a.warmup, a.source, not a.materialize_xp, a.yp_dtype, a.early_static)
             log(json.dumps(r))
-            others[name] = {k: r[k] for k in ("R", "ms_per_step", "ffn_tflops_kernels", "pct_mfma_peak_ffn_kernels",
-                                              "gate_up_tflops", "down_tflops", "combine_gbps", "route_gbps",
-                                              "permute_gbps", "graph_replay_ms_per_step") if k in r}
+            others[name] = _summary(r)
             q.wl.drop_weights()
             del q
             torch.cuda.empty_cache()
-    up_tflops = res["gate_up_tflops"]
+    # the other workload the grouped-FFN target names: the skewed share, a 0.9 ms step
+    if not a.all and a.workload != "C3" and not a.no_c3:
+        p.wl.drop_weights()
+        del p
+        torch.cuda.empty_cache()
+        q, r = time_workload("C3", a.steps, a.warmup, a.source, not a.materialize_xp, a.yp_dtype, a.early_static)
+        log(json.dumps(r))
+        others["C3"] = _summary(r)
+        q.wl.drop_weights()
+        del q
+        torch.cuda.empty_cache()
     out = {
         "metric": METRIC, "value": res["ffn_tflops_step"], "unit": "TFLOP/s", "n_gpus": 1,
         "steps": a.steps, "warmup": a.warmup, "ms_per_step": res["ms_per_step"], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{a.workload} ({_describe(a.workload)})", "T": res["T"], "R": res["R"],
                    "d": res["d"], "f": res["f"], "E": res["E"], "k": res["k"], "groups": res["groups"],
+                   "nonempty_groups": res["nonempty_groups"],
                    "yp_dtype": a.yp_dtype, "x_rows": "permuted copy" if a.materialize_xp else "gathered by the gate/up GEMM",
                    "schedule": ("static experts launched before the plan" if a.early_static else "plan first") if a.workload == "C4" else None,
                    "staging_source": a.source if a.workload == "C4" else None},
-        "roofline": {"kernel": "grouped_gemm_kernel<0,true,false> (gate/up GEMM + SwiGLU)", "bound": "mfma",
-                     "achieved": up_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": up_tflops / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(a.workload),
-                     "traffic_unit": "bytes per launch (HBM read + write, rocprofv3 --pmc, profiles/hbm_traffic_C4_pmc.md)",
-                     "algorithmic_bytes_per_launch": _gate_up_min_bytes(res),
-                     "launches_per_step": res["gate_up_launches_per_step"],
-                     "avg_launch_ms": res["gate_up_ms_per_launch"],
-                     "flops_per_launch": 4.0 * res["d"] * res["f"] * res["R"] / res["gate_up_launches_per_step"]},
+        "roofline": res["rooflines"]["gate_up"],
+        "rooflines": {k: v for k, v in res["rooflines"].items() if k != "gate_up"},
         "cpu_baseline": cpu,
         "ffn_training_step": training,
-        "detail": {k: res[k] for k in res if k not in ("workload",)},
+        "detail": {k: res[k] for k in res if k not in ("workload", "rooflines")},
         "device": _device_info(prop),
     }
     if others:
-        out["all_workloads"] = others
+        out["other_workloads"] = others
     print(json.dumps(out), flush=True)
 
 
-def _gate_up_min_bytes(res):
-    """Unique operand bytes of the gate/up GEMM per launch: both weight matrices of every
-    non-empty group once, every token row of the launch once, H written once (averaged over the launches of a step)."""
-    groups = res.get("nonempty_groups", res["groups"])
-    total = groups * 2 * res["d"] * res["f"] * 2 + res["R"] * res["d"] * 2 + res["R"] * res["f"] * 2
-    return total / res["gate_up_launches_per_step"]
+def _summary(r):
+    """The figures of a secondary workload: step time, both GEMMs with their fraction of the MFMA peak, the
+    bandwidth kernels with theirs."""
+    rf = r["rooflines"]
+    out = {k: r[k] for k in ("R", "nonempty_groups", "ms_per_step", "ffn_tflops_kernels", "pct_mfma_peak_ffn_kernels",
+                             "graph_replay_ms_per_step") if k in r}
+    for key in ("gate_up", "down"):
+        out[key] = {"tflops": rf[key]["achieved"], "frac": rf[key]["frac"], "avg_launch_ms": rf[key]["avg_launch_ms"]}
+    for key in ("combine", "permute_with_gather", "route"):
+        out[key] = {"achieved": rf[key]["achieved"], "unit": rf[key]["unit"], "frac": rf[key]["frac"], "ms": rf[key]["avg_launch_ms"]}
+    return out
 
 
 def _device_info(prop):

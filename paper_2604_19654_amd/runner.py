@@ -86,11 +86,11 @@ def prepare(name: str, device="cuda:0", yp_dtype=torch.float32, source_kind="dev
                     moves, source_kind)
 
 
-def step(p: Prepared, mark=False, overlap=True, early_static=False):
+def step(p: Prepared, mark=False, overlap=True, early_static=True):
     """One pass of the whole hot path over the workload's batch. Returns Y (bf16 [T,d]).
-    Rebalanced share: by default the plan comes first and one permute covers all groups;
-    early_static launches the static experts' permute and FFN before the host has the plan and
-    appends the replicas' groups behind the static FFN (needs overlap)."""
+    Rebalanced share: by default the timeline of Section 2.3 -- the static experts' permute and
+    FFN are launched before the host has the plan, the replicas' groups are appended behind the
+    static FFN (needs overlap).  early_static=False plans first and permutes all groups at once."""
     wl = p.wl
     if not p.rebalanced:
         return p.layer.forward(wl.logits, wl.X, p.groups, p.weights, mark=mark)

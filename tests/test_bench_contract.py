@@ -40,4 +40,16 @@ def test_one_json_line_with_the_agreed_keys():
     cpu = d["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["cores"] >= 1 and cpu["value"] > 0 and cpu["integer_outputs_match"] is True
     assert d["value"] > 0 and d["ms_per_step"] > 0
+    assert cpu["parity"] is True and cpu["rows_above_row_bar"] == 0 and cpu["worst_element_over_storage_format_bound"] <= 1.0
+    assert cpu["host_cpus"] >= cpu["cores"] >= 1
+    # one roofline object per kernel of the step, each recomputable from its own fields
+    assert set(d["rooflines"]) == {"down", "combine", "permute_with_gather", "row_gather_alone", "route"}
+    for key, r in list(d["rooflines"].items()) + [("gate_up", roof)]:
+        assert r["bound"] in ("mfma", "hbm", "alu") and abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-9, key
+        assert r["avg_launch_ms"] > 0
+    assert roof["per_launch"][0]["nonempty_groups"] == d["config"]["nonempty_groups"] == 8
+    assert abs(roof["flops_per_launch"] / (roof["avg_launch_ms"] * 1e-3) / 1e12 - roof["achieved"]) < 1e-6 * roof["achieved"]
+    # the skewed share is timed in the default run as well
+    c3 = d["other_workloads"]["C3"]
+    assert c3["gate_up"]["frac"] > 0 and c3["down"]["frac"] > 0 and c3["R"] > 8192
     assert d["ffn_training_step"]["ms"]["backward"] > 0
