@@ -251,22 +251,21 @@ def test_backward_at_full_size_on_sampled_outputs(name):
         dx_o = orc.ffn_rows_backward(f64(Xp[rows]), Wg, Wu, Wd, f64(dYp[rows]))[0]
         e = check_rows(f64(st.dXp[rows]), dx_o, f"{name}: dXp rows of group {g}")
         worst[:2] = np.maximum(worst[:2], e)
-        # columns j of the gate and up gradients (transposed: one row per sampled column)
+        # Sampled columns through the oracle itself.  The expert is separable over its hidden units
+        # (y = sum_j h_j Wd[j,:]), so the oracle run on the sub-expert made of hidden units `cols`
+        # (Wg[:, cols], Wu[:, cols], Wd[cols, :]) with the same dy returns exactly the columns `cols` of
+        # dWg and dWu; and run on the output columns `dcols` alone (Wd[:, dcols], dy[:, dcols]) it returns
+        # exactly those columns of dWd.  (One row per sampled column below.)
         cols = [0, st.f // 2 + 1, st.f - 1]
         X64, dY64 = f64(Xp[lo:hi]), f64(dYp[lo:hi])
-        a, b = X64 @ Wg[:, cols], X64 @ Wu[:, cols]
-        sg = 1.0 / (1.0 + np.exp(-a))
-        dh = dY64 @ Wd[cols, :].T
-        da, db = dh * b * sg * (1.0 + a * (1.0 - sg)), dh * a * sg
-        e = check_rows(f64(st.dW_gate[g][:, cols]).T, (X64.T @ da).T, f"{name}: dW_gate[{g}] columns")
+        _, dWg_c, dWu_c, _ = orc.ffn_rows_backward(X64, Wg[:, cols], Wu[:, cols], Wd[cols, :], dY64)
+        e = check_rows(f64(st.dW_gate[g][:, cols]).T, dWg_c.T, f"{name}: dW_gate[{g}] columns")
         worst[2:] = np.maximum(worst[2:], e)
-        e = check_rows(f64(st.dW_up[g][:, cols]).T, (X64.T @ db).T, f"{name}: dW_up[{g}] columns")
+        e = check_rows(f64(st.dW_up[g][:, cols]).T, dWu_c.T, f"{name}: dW_up[{g}] columns")
         worst[2:] = np.maximum(worst[2:], e)
-        # columns of the down gradient: dWd[:, c] = H^T dYp[:, c]
         dcols = [0, st.d // 2 + 1, st.d - 1]
-        a_all, b_all = X64 @ Wg, X64 @ Wu
-        h = a_all / (1.0 + np.exp(-a_all)) * b_all
-        e = check_rows(f64(st.dW_down[g][:, dcols]).T, (h.T @ dY64[:, dcols]).T, f"{name}: dW_down[{g}] columns")
+        dWd_c = orc.ffn_rows_backward(X64, Wg, Wu, Wd[:, dcols], dY64[:, dcols])[3]
+        e = check_rows(f64(st.dW_down[g][:, dcols]).T, dWd_c.T, f"{name}: dW_down[{g}] columns")
         worst[2:] = np.maximum(worst[2:], e)
         say(f"  group {g} ({hi - lo} rows) checked")
     for g in np.nonzero(sizes == 0)[0][:3]:

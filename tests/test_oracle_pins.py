@@ -877,3 +877,19 @@ def test_apply_moves_gives_the_planned_loads():
     home = orc.apply_moves(owner, moves)
     assert np.array_equal(orc.rank_loads(P, home, n), after)
     assert np.array_equal(orc.apply_moves(owner, []), owner)
+
+
+def test_ffn_backward_is_separable_over_hidden_units_and_output_columns():
+    # what the full-size GPU test relies on to reach the oracle with sampled columns: the sub-expert made of
+    # some hidden units yields exactly those columns of dWg and dWu; restricting the output columns yields
+    # exactly those columns of dWd
+    rng = np.random.default_rng(0)
+    m, d, f = 7, 12, 10
+    x, dy = rng.normal(size=(m, d)), rng.normal(size=(m, d))
+    wg, wu, wd = rng.normal(size=(d, f)), rng.normal(size=(d, f)), rng.normal(size=(f, d))
+    _, dWg, dWu, dWd = orc.ffn_rows_backward(x, wg, wu, wd, dy)
+    cols, dcols = [0, 6, 9], [1, 11]
+    _, a, b, _ = orc.ffn_rows_backward(x, wg[:, cols], wu[:, cols], wd[cols, :], dy)
+    c = orc.ffn_rows_backward(x, wg, wu, wd[:, dcols], dy[:, dcols])[3]
+    assert np.allclose(a, dWg[:, cols], rtol=1e-13, atol=1e-13) and np.allclose(b, dWu[:, cols], rtol=1e-13, atol=1e-13)
+    assert np.allclose(c, dWd[:, dcols], rtol=1e-13, atol=1e-13)
