@@ -29,8 +29,14 @@ HBM_PEAK_GBPS = 8000.0           # MI355X HBM3E
 # The figures belong to the kernel source they were measured on: bench.py reports them only while
 # csrc/ffn.hip still has that content (sha256), and null otherwise.
 MEASURED_TRAFFIC = {
-    "C4": {"profile": "profiles/hbm_traffic_C4_pmc.md", "ffn_hip_sha256": "UNMEASURED",
-           "gate_up": {"read": 5.103e9, "written": 0.268e9}, "down": None},
+    "C4": {"profile": "profiles/hbm_traffic_C4_C3_pmc.md",
+           "ffn_hip_sha256": "e220b4efd4c5d5adfadee6c4b4c8fb1beb505f7a128794e6795867ee6e9636ce",
+           "gate_up": {"read": 2496533 * 1024 * 2.0, "written": 262140 * 1024},       # FETCH_SIZE KiB x 2.000, WRITE_SIZE KiB
+           "down": {"read": 1271943 * 1024 * 2.0, "written": 1573573 * 1024}},
+    "C3": {"profile": "profiles/hbm_traffic_C4_C3_pmc.md",
+           "ffn_hip_sha256": "e220b4efd4c5d5adfadee6c4b4c8fb1beb505f7a128794e6795867ee6e9636ce",
+           "gate_up": {"read": 454829 * 1024 * 2.0, "written": 61188 * 1024},
+           "down": {"read": 227325 * 1024 * 2.0, "written": 326958 * 1024}},
 }
 METRIC = "grouped-FFN TFLOP/s & % bf16 MFMA peak per rank share; permute/combine GB/s"
 
