@@ -5,12 +5,14 @@ A step is one pass of the whole path (route -> [plan + staging] -> permute ->
 grouped SwiGLU FFN -> combine) over one synthetic batch that is already
 resident in HBM.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4] [--no-cpu-baseline] [--all]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4] [--no-cpu-baseline] [--only]
 
 value      = FFN flops of the step (6*d*f per permuted row) / wall time of the WHOLE step
 roofline   = the gate/up GEMM (the dominant kernel): 4*d*f flops per row over its
              average launch duration, measured with HIP events on the launch stream
-cpu_baseline = the CPU oracle timed on a bounded sample of the same workload
+rooflines  = the same kind of object for the down GEMM, the combine, the permute step, the router
+cpu_baseline = the CPU oracle timed on a bounded sample of the same workload, with the parity verdict
+other_workloads = the four other workloads as short forward-only runs (skipped with --only)
 """
 import argparse
 import json
@@ -398,8 +400,9 @@ def main():
     ap.add_argument("--workload", default="C4")
     ap.add_argument("--source", default="device", choices=["device", "pinned"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--all", action="store_true", help="also time the other four workloads (reported under other_workloads)")
-    ap.add_argument("--no-c3", action="store_true", help="skip the skewed share C3 that the default run times after the main workload")
+    ap.add_argument("--only", "--no-c3", dest="only", action="store_true",
+                    help="time the named workload only (default: the other four follow as short forward-only runs, reported under other_workloads)")
+    ap.add_argument("--all", action="store_true", help="(kept for old command lines: all five workloads are the default now)")
     ap.add_argument("--cpu-tokens", type=int, default=65536)
     ap.add_argument("--no-training", action="store_true", help="skip the FFN training-step leg (forward keeping the SwiGLU derivatives, backward)")
     ap.add_argument("--yp-dtype", default="f32", choices=["f32", "bf16"],
@@ -430,28 +433,18 @@ def main():
         training = training_leg(p, a.steps)
         log(json.dumps(training))
         torch.cuda.empty_cache()
+    # the other four workloads, each a short run of its own (forward step only): C3 is the other share the
+    # grouped-FFN target names; C2, C5 and C1 complete the record
     others = {}
-    if a.all:
-        p.wl.drop_weights()
-        del p
-        torch.cuda.empty_cache()
-        for name in ("C1", "C2", "C3", "C5", "C4"):
-            if name == a.workload:
-                continue
-            q, r = time_workload(name, a.steps, a.warmup, a.source, not a.materialize_xp, a.yp_dtype, a.early_static)
-            log(json.dumps(r))
-            others[name] = _summary(r)
-            q.wl.drop_weights()
-            del q
-            torch.cuda.empty_cache()
-    # the other workload the grouped-FFN target names: the skewed share, a 0.9 ms step
-    if not a.all and a.workload != "C3" and not a.no_c3:
-        p.wl.drop_weights()
-        del p
-        torch.cuda.empty_cache()
-        q, r = time_workload("C3", a.steps, a.warmup, a.source, not a.materialize_xp, a.yp_dtype, a.early_static)
+    p.wl.drop_weights()
+    del p
+    torch.cuda.empty_cache()
+    for name in () if a.only else ("C3", "C2", "C5", "C1", "C4"):
+        if name == a.workload:
+            continue
+        q, r = time_workload(name, a.steps, a.warmup, a.source, not a.materialize_xp, a.yp_dtype, a.early_static)
         log(json.dumps(r))
-        others["C3"] = _summary(r)
+        others[name] = _summary(r)
         q.wl.drop_weights()
         del q
         torch.cuda.empty_cache()

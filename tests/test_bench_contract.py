@@ -49,7 +49,8 @@ def test_one_json_line_with_the_agreed_keys():
         assert r["avg_launch_ms"] > 0
     assert roof["per_launch"][0]["nonempty_groups"] == d["config"]["nonempty_groups"] == 8
     assert abs(roof["flops_per_launch"] / (roof["avg_launch_ms"] * 1e-3) / 1e12 - roof["achieved"]) < 1e-6 * roof["achieved"]
-    # the skewed share is timed in the default run as well
+    # the other four workloads are timed in the default run as well
+    assert set(d["other_workloads"]) == {"C2", "C3", "C4", "C5"}
     c3 = d["other_workloads"]["C3"]
     assert c3["gate_up"]["frac"] > 0 and c3["down"]["frac"] > 0 and c3["R"] > 8192
     assert d["ffn_training_step"]["ms"]["backward"] > 0
