@@ -52,6 +52,13 @@ __global__ __launch_bounds__(BLOCK) void combine_kernel(const void* __restrict__
     if (my_row >= R_cap) my_row = -1;   // a row past the capacity was never computed: not local
   }
   const unsigned long long local = __ballot(my_row >= 0);
+  if (local == 0) {
+    // no local slot (most tokens of a rank's share): the row is +0, written with 16-byte stores
+    const int n16 = d / 8;
+    u32x4* row = (u32x4*)Y + t * n16;
+    for (int c = lane; c < n16; c += 64) __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, row + c);
+    return;
+  }
   for (int c0 = 0; c0 < nchunk; c0 += 64 * UNROLL) {
     float acc[UNROLL][PER];
 #pragma unroll
