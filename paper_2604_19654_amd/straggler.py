@@ -188,15 +188,19 @@ def study(P: int, dyn_list: Sequence[int], n_batches: int, tokens_per_rank: int 
 
 def predictor_study(P: int, dyn: int, n_batches: int, warm: int, shift: int = 2, tokens_per_rank: int = 16384,
                     E: int = 128, k: int = 8, d: int = 6144, f: int = 2048, tau: int = 0, seed0: int = 7000,
-                    device="cuda:0", with_gemm: bool = True, keep_records: bool = False) -> Dict:
+                    device="cuda:0", with_gemm: bool = True, keep_records: bool = False, drift: int = 0,
+                    replace_every: int = 0) -> Dict:
     """Macro level of Section 2.3 on synthetic routing whose popularity persists over the micro-batches
     of a run (one popularity seed, new logit noise per batch).  The first `warm` batches only feed the
     library's routing history; then the library derives a new expert -> rank map from it
     (feplb_place) and marks each rank's `dyn` busiest experts as dynamic (feplb_mark_dynamic).  On the
     remaining batches the token straggler (and, from the per-rank FFN times, the GEMM straggler) is
     reported for four set-ups: the contiguous map, the contiguous map with the per-micro-batch plan,
-    the placed map, the placed map with the plan.  Sequencing only: routing, history, placement,
-    plan and FFN are library calls."""
+    the placed map, the placed map with the plan.  With drift > 0 that many random pairs of experts
+    exchange their popularity between one micro-batch and the next, so the history lags behind;
+    with replace_every > 0 the map is derived anew from the history after every so many measured
+    micro-batches (the paper's "periodically"), starting from the map then in use.
+    Sequencing only: routing, history, placement, plan and FFN are library calls."""
     T = P * tokens_per_rank
     per = E // P
     hist = np.zeros(E, dtype=np.int64)
@@ -209,7 +213,8 @@ def predictor_study(P: int, dyn: int, n_batches: int, warm: int, shift: int = 2,
     timer = None
     slots = np.full(P, dyn, dtype=np.int32)
     for b in range(n_batches):
-        wl = workloads.make("C4", device=device, seed=seed0 + b, pop_seed=seed0, P=P, T=T, d=8, f=8, E=E, k=k)
+        wl = workloads.make("C4", device=device, seed=seed0 + b, pop_seed=seed0, drift_swaps=b * drift, P=P, T=T, d=8, f=8,
+                            E=E, k=k)
         _ids, _w, counts_dev = B.feplb_route_topk(wl.logits, k)
         torch.cuda.synchronize()
         counts = counts_dev.cpu().numpy().astype(np.int64)
@@ -221,7 +226,7 @@ def predictor_study(P: int, dyn: int, n_batches: int, warm: int, shift: int = 2,
         if placed is None:
             owner1, load_before, load_after, migrated = B.feplb_place(P, hist, per, owner0)
             placed = dict(owner=owner1, predicted_before=load_before, predicted_after=load_after, migrated=migrated,
-                          hist=hist.copy())
+                          hist=hist.copy(), placements=[(b, migrated)])
         rec = {"seed": seed0 + b, "counts": counts, "loads": {}, "token_straggler": {}}
         records.append(rec)
         for name, owner in (("contiguous", owner0), ("placed", placed["owner"])):
@@ -235,7 +240,13 @@ def predictor_study(P: int, dyn: int, n_batches: int, warm: int, shift: int = 2,
                         timer = FfnTimer(d, f, max_rows=int(counts.sum()), max_groups=min(E, B.MAX_GROUPS), device=device)
                     gemm[key].append(straggler([timer.time_ms(s) for s in placement(P, owner, counts, mv)]))
         B.feplb_history_update(hist, counts, shift)
-    out = {"P": P, "dyn": dyn, "batches": n_batches, "warm": warm, "shift": shift, "tokens_per_rank": tokens_per_rank,
+        if replace_every > 0 and (b - warm + 1) % replace_every == 0 and b + 1 < n_batches:
+            owner1, _lb, _la, migrated = B.feplb_place(P, hist, per, placed["owner"])
+            placed["owner"] = owner1
+            placed["migrated"] += migrated
+            placed["placements"].append((b + 1, migrated))
+    out = {"P": P, "dyn": dyn, "batches": n_batches, "warm": warm, "shift": shift, "drift": drift, "replace_every": replace_every,
+           "tokens_per_rank": tokens_per_rank,
            "E": E, "k": k, "migrated_experts": placed["migrated"],
            "predicted_max_load_rows": {"contiguous": float(placed["predicted_before"].max()) / (1 << B.HIST_FRAC_BITS),
                                        "placed": float(placed["predicted_after"].max()) / (1 << B.HIST_FRAC_BITS)},
@@ -266,13 +277,17 @@ def main():
                     help="macro level: routing whose popularity persists over the micro-batches; history -> placement, "
                          "then the four set-ups (contiguous / placed map, without / with the per-micro-batch plan)")
     ap.add_argument("--warm", type=int, default=4, help="micro-batches that only feed the history (--predictor)")
+    ap.add_argument("--replace-every", type=int, default=0,
+                    help="derive the map anew from the history after every so many measured micro-batches (--predictor; 0: once)")
+    ap.add_argument("--drift", type=int, default=0,
+                    help="pairs of experts that exchange their popularity between one micro-batch and the next (--predictor)")
     a = ap.parse_args()
     B.lib()
     if a.predictor:
         rows = []
         for P in a.ep:
             r = predictor_study(P, 4, a.batches + a.warm, a.warm, tokens_per_rank=a.tokens_per_rank, d=a.d, f=a.f, tau=a.tau,
-                                with_gemm=not a.no_gemm)
+                                with_gemm=not a.no_gemm, drift=a.drift, replace_every=a.replace_every)
             rows.append(r)
             print(json.dumps(r), flush=True)
         print("\n| EP | experts migrated | token straggler: contiguous | + plan | placed | placed + plan | GEMM straggler (ms): contiguous | + plan | placed | placed + plan |")

@@ -27,11 +27,11 @@ def test_token_bookkeeping_matches_the_oracle(P, dyn, seed):
     assert [sum(s) for s in st.placement(P, owner, counts, [])] == [int(x) for x in before]
 
 
-def oracle_counts(P, T, seed, pop_seed=None):
+def oracle_counts(P, T, seed, pop_seed=None, drift_swaps=0):
     """The same micro-batch as the study's, routed by the oracle on the host (the generator's
     bits do not depend on the device for the host-drawn popularity; the logit noise is drawn
     on the device the study uses, so the caller passes that device's logits where it matters)."""
-    kw = {} if pop_seed is None else {"pop_seed": pop_seed}
+    kw = {} if pop_seed is None else {"pop_seed": pop_seed, "drift_swaps": drift_swaps}
     return workloads.make("C4", device="cuda:0", seed=seed, P=P, T=T, d=8, f=8, **kw)
 
 
@@ -63,9 +63,9 @@ def test_small_study_runs_and_reduces_both_stragglers():
 
 @pytest.mark.gpu
 def test_predictor_study_matches_the_oracle_and_the_placement_helps():
-    P, tokens, dyn, warm, shift, seed0 = 4, 4096, 4, 3, 2, 7100
+    P, tokens, dyn, warm, shift, seed0, drift = 4, 4096, 4, 3, 2, 7100, 1
     r = st.predictor_study(P=P, dyn=dyn, n_batches=warm + 3, warm=warm, shift=shift, tokens_per_rank=tokens,
-                           d=512, f=256, seed0=seed0, keep_records=True)
+                           d=512, f=256, seed0=seed0, keep_records=True, drift=drift, replace_every=2)
     # oracle leg: route every batch on the CPU, keep the history, place, plan
     E = 128
     hist = np.zeros(E, dtype=np.int64)
@@ -73,15 +73,16 @@ def test_predictor_study_matches_the_oracle_and_the_placement_helps():
     owner1 = None
     recs = iter(r["records"])
     for b in range(warm + 3):
-        wl = oracle_counts(P, P * tokens, seed0 + b, pop_seed=seed0)
+        wl = oracle_counts(P, P * tokens, seed0 + b, pop_seed=seed0, drift_swaps=b * drift)
         _, _, counts = orc.route_topk(wl.logits.cpu().numpy(), wl.k)
         if b < warm:
             hist = orc.history_update(hist, counts, shift if b else 0)
             continue
         if owner1 is None:
             owner1, pb, pa, migrated = orc.place_lpt(P, hist, E // P, wl.owner())
-            assert np.array_equal(r["placed"]["owner"], owner1) and r["migrated_experts"] == migrated
+            assert r["placed"]["placements"][0] == (b, migrated)
             assert np.array_equal(r["placed"]["hist"], hist)
+            total_migrated = migrated
             assert np.bincount(owner1, minlength=P).tolist() == [E // P] * P
         rec = next(recs)
         assert np.array_equal(rec["counts"], counts)
@@ -92,6 +93,10 @@ def test_predictor_study_matches_the_oracle_and_the_placement_helps():
             assert rec["token_straggler"][name] == orc.token_straggler(before)
             assert rec["token_straggler"][name + "+plan"] == orc.token_straggler(after)
         hist = orc.history_update(hist, counts, shift)
+        if (b - warm + 1) % 2 == 0 and b + 1 < warm + 3:                       # replace_every = 2
+            owner1, _, _, migrated = orc.place_lpt(P, hist, E // P, owner1)
+            total_migrated += migrated
+    assert np.array_equal(r["placed"]["owner"], owner1) and r["migrated_experts"] == total_migrated
     t = r["token_straggler"]
     # a popularity that persists is what the placement learns: it must beat the contiguous map on the later batches
     assert t["placed"] < t["contiguous"] and t["placed+plan"] <= t["placed"] and t["contiguous+plan"] <= t["contiguous"]

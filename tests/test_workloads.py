@@ -56,3 +56,13 @@ def test_popularity_seed_persists_over_micro_batches():
     assert np.allclose(b.logits.numpy() - b.bias.astype(np.float32), c.logits.numpy() - c.bias.astype(np.float32), atol=1e-4)
     # without pop_seed nothing changes
     assert np.array_equal(workloads.make("C3", T=64, d=8, f=8).bias, workloads.make("C3", T=64, d=8, f=8, pop_seed=1003).bias)
+
+
+def test_popularity_drifts_by_one_pair_per_swap():
+    base = workloads.make("C4", T=64, d=8, f=8, seed=9, pop_seed=3)
+    prev = base.bias
+    for n in range(1, 6):
+        cur = workloads.make("C4", T=64, d=8, f=8, seed=9 + n, pop_seed=3, drift_swaps=n).bias
+        assert sorted(cur.tolist()) == sorted(base.bias.tolist())          # the same popularities, re-assigned
+        assert (cur != prev).sum() in (0, 2)                                # one more pair exchanged (or a pair (i, i))
+        prev = cur

@@ -20,7 +20,9 @@ seed s) -> token rows X (torch, seed s + 1) -> expert e's weights (torch,
 seed ``(s + 2) * 4096 + e``, gate then up then down), drawn on demand so that
 only the experts a rank actually runs are ever materialised.  With ``pop_seed=``
 the popularity is drawn from that seed instead, so that a series of micro-batches
-(seeds s, s+1, ...) shares one popularity, as the batches of one training run do.
+(seeds s, s+1, ...) shares one popularity, as the batches of one training run do;
+``drift_swaps=n`` exchanges the popularity ranks of n random expert pairs on top,
+so that batch b with ``drift_swaps=b*m`` sees a popularity that moves by m pairs per batch.
 """
 from __future__ import annotations
 
@@ -116,9 +118,15 @@ class Workload:
         self._wcache.clear()
 
 
-def _zipf_bias(E: int, rng: np.random.Generator):
-    """b_e = 2.0 * ln(rank_e ** -1.2), rank_e a seeded permutation of 1..E."""
+def _zipf_bias(E: int, rng: np.random.Generator, drift_swaps: int = 0):
+    """b_e = 2.0 * ln(rank_e ** -1.2), rank_e a seeded permutation of 1..E.  With drift_swaps > 0 that
+    many random pairs of experts then exchange their popularity ranks, one pair after the other, drawn
+    from the same generator: the popularity after n swaps is the one after n - 1 with one more pair
+    exchanged, so a series of growing counts is a popularity that drifts."""
     rank_e = rng.permutation(E) + 1
+    for _ in range(drift_swaps):
+        i, j = rng.integers(0, E, size=2)
+        rank_e[i], rank_e[j] = rank_e[j], rank_e[i]
     return 2.0 * np.log(rank_e.astype(np.float64) ** -1.2), rank_e
 
 
@@ -151,6 +159,7 @@ def make(name: str, device="cpu", **override) -> Workload:
     # the experts' popularity may keep its own seed while the logit noise, tokens and weights
     # follow `seed`: micro-batches of one training run share a popularity and differ in the rest
     pop_seed = int(override.pop("pop_seed", seed))
+    drift_swaps = int(override.pop("drift_swaps", 0))     # Zipf popularity only: see _zipf_bias
     p.update(override)
     T, d, f, E, k, P = (int(p[x]) for x in ("T", "d", "f", "E", "k", "P"))
     if E % P:
@@ -163,7 +172,7 @@ def make(name: str, device="cpu", **override) -> Workload:
     if p["pop"] == "uniform":
         bias = np.zeros(E)
     elif p["pop"] == "zipf":
-        bias, rank_e = _zipf_bias(E, rng)
+        bias, rank_e = _zipf_bias(E, rng, drift_swaps)
         if p["rank"] == 0:
             # Make rank 0 the rank with the most popular experts by relabelling,
             # not by re-drawing: exchange column block 0 with the block whose
