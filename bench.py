@@ -171,6 +171,7 @@ def time_workload(name, steps, warmup, source_kind="device", fused_gather=True, 
         res["moves"] = p.moves
     res["pct_mfma_peak_ffn_kernels"] = 100.0 * res["ffn_tflops_kernels"] / MFMA_BF16_PEAK_TFLOPS
     res["reference_copy_gbps"] = _reference_copy_gbps(layer.buf.Y)
+    res["reference_dense_gemm"] = _reference_dense_gemm(R, d, f, wl.X.device)
     res["rooflines"] = _rooflines(name, res)
     return p, res
 
@@ -189,6 +190,37 @@ def _reference_copy_gbps(buf):
     e1.record(None)
     e1.synchronize()
     return 2 * buf.numel() * buf.element_size() / (e0.elapsed_ms(e1) / 10 * 1e-3) / 1e9
+
+
+def _reference_dense_gemm(R, d, f, device):
+    """Context only, never part of the path: what the vendor library's plain dense bf16 GEMM (torch.matmul) reaches
+    on this machine for one matrix product of the gate/up GEMM's size, [R, d] x [d, 2f], and one of the down GEMM's
+    size, [R, f] x [f, d] -- one group each, no ragged tiles, no row gather, no SwiGLU, bf16 output."""
+    import torch
+    from paper_2604_19654_amd import binding as B
+    out = {"what": "torch.matmul, bf16 in and out, one dense product of each GEMM's size"}
+    try:
+        gen = torch.Generator(device=device)
+        gen.manual_seed(99)
+        for key, (m, kk, n) in (("gate_up", (R, d, 2 * f)), ("down", (R, f, d))):
+            a = torch.empty((m, kk), dtype=torch.float32, device=device).normal_(generator=gen).to(torch.bfloat16)
+            w = (torch.empty((kk, n), dtype=torch.float32, device=device).normal_(generator=gen) * 0.02).to(torch.bfloat16)
+            c = torch.empty((m, n), dtype=torch.bfloat16, device=device)
+            e0, e1 = B.HipEvent(), B.HipEvent()
+            for _ in range(3):
+                torch.matmul(a, w, out=c)
+            e0.record(None)
+            for _ in range(5):
+                torch.matmul(a, w, out=c)
+            e1.record(None)
+            e1.synchronize()
+            ms = e0.elapsed_ms(e1) / 5
+            tf = 2.0 * m * kk * n / (ms * 1e-3) / 1e12
+            out[key] = {"shape": [m, kk, n], "ms": ms, "tflops": tf, "frac_of_mfma_peak": tf / MFMA_BF16_PEAK_TFLOPS}
+            del a, w, c
+    except Exception as exc:      # a reference figure must never break the benchmark
+        out["error"] = str(exc)
+    return out
 
 
 def _traffic(name, kernel):
