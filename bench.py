@@ -58,16 +58,19 @@ def time_workload(name, steps, warmup, source_kind="device", fused_gather=True, 
     for _ in range(warmup):
         runner.step(p, mark=True, early_static=early_static)
     torch.cuda.synchronize()
-    tl = layer.timeline
-    acc = {}
-    per_step = []
+    # Every timed step records into an event set of its own, read after the last step has drained: the host
+    # never waits between steps (a rebalanced step still waits, inside the step, for its counts read-back).
+    timelines = []
     t0 = time.perf_counter()
     for _ in range(steps):
+        layer.timeline = {}
         runner.step(p, mark=True, early_static=early_static)
-        # the step's events are complete once the stream drains; reading them costs one sync per
-        # step, which a rebalanced step already pays for its counts read-back
-        tl["combined"].synchronize()
-
+        timelines.append(layer.timeline)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    acc = {}
+    per_step = []
+    for tl in timelines:
         def span(a, b, key):
             if a in tl and b in tl:
                 acc[key] = acc.get(key, 0.0) + tl[a].elapsed_ms(tl[b])
@@ -79,7 +82,7 @@ def time_workload(name, steps, warmup, source_kind="device", fused_gather=True, 
             span("static_gate_up", "static_down", "down")
             span("dynamic_scheduled", "dynamic_gate_up", "gate_up")
             span("dynamic_gate_up", "dynamic_down", "down")
-            acc["copy"] = acc.get("copy", 0.0) + _copy_ms(layer)
+            span("copy_start", "copy_end", "copy")
             span("static_down", "staged", "wait_for_copy")
             span("dynamic_done", "combined", "combine")
             # plan first: counts read-back, host plan and the permute of all groups; early static
@@ -90,8 +93,7 @@ def time_workload(name, steps, warmup, source_kind="device", fused_gather=True, 
             span("static_scheduled", "static_gate_up", "gate_up")
             span("static_gate_up", "static_down", "down")
             span("static_down", "combined", "combine")
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    acc.setdefault("copy", 0.0)
     ms = {k: v / steps for k, v in acc.items() if not k.startswith("_")}
     n_up = 2 if (p.rebalanced and len(p.groups) > len(p.static_weights)) else 1
     R, d, f, T, k = p.R, wl.d, wl.f, wl.T, wl.k
@@ -338,15 +340,6 @@ def training_leg(p, steps):
                 backward_over_forward=ms["backward"] / ms["forward_keeping_derivatives"],
                 note="backward = weight transposes + dH GEMM with the SwiGLU derivative + dXp GEMM + three ragged "
                      "weight-gradient GEMMs (fp32 out); upstream gradient synthetic; Xp materialised")
-
-
-def _copy_ms(layer):
-    tl = layer.timeline
-    if "copy_start" not in tl:
-        return 0.0
-    start, end = tl["copy_start"], layer.staged
-    end.synchronize()
-    return start.elapsed_ms(end)
 
 
 def cpu_baseline(p, budget_tokens):

@@ -201,6 +201,8 @@ class RankLayer:
             for i, (e, *_rest) in enumerate(moves):
                 B.feplb_stage_weights(b.slots[i], remote_sources[e], side, None)
             self.staged.record(side)
+            if mark:
+                self.timeline.setdefault("copy_end", B.HipEvent()).record(side)
             # the append on a stream of its own: its small kernels wait for compute units the
             # static GEMM holds, and the copies must not queue behind them
             aux = self.append_stream
@@ -255,6 +257,8 @@ class RankLayer:
         for i, (e, *_rest) in enumerate(moves):
             last = i == len(moves) - 1
             B.feplb_stage_weights(b.slots[i], remote_sources[e], side, self.staged if last else None)
+        if mark and moves:
+            self.timeline.setdefault("copy_end", B.HipEvent()).record(side)
         wlist = [static_weights[e] for e in static] + [self.slot_views(i) for i in range(len(moves))]
         wg, wu, wd = ([w[i] for w in wlist] for i in range(3))
         self._ffn_range(X, 0, Gs, wg, wu, wd, "static", mark)
