@@ -60,12 +60,16 @@ def time_workload(name, steps, warmup, source_kind="device", fused_gather=True, 
     torch.cuda.synchronize()
     # Every timed step records into an event set of its own, read after the last step has drained: the host
     # never waits between steps (a rebalanced step still waits, inside the step, for its counts read-back).
-    timelines = []
+    # (The event sets are created here, before the clock starts: creating events inside the timed loop can
+    # make the runtime grow its signal pool in the middle of a step.)
+    from paper_2604_19654_amd import binding as B
+    names = list(layer.timeline)
+    timelines = [{n: B.HipEvent() for n in names} for _ in range(steps)]
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(steps):
-        layer.timeline = {}
+    for tl in timelines:
+        layer.timeline = tl
         runner.step(p, mark=True, early_static=early_static)
-        timelines.append(layer.timeline)
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / steps
     acc = {}
