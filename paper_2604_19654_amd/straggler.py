@@ -201,6 +201,8 @@ def predictor_study(P: int, dyn: int, n_batches: int, warm: int, shift: int = 2,
     with replace_every > 0 the map is derived anew from the history after every so many measured
     micro-batches (the paper's "periodically"), starting from the map then in use.
     Sequencing only: routing, history, placement, plan and FFN are library calls."""
+    if not 0 < warm < n_batches:
+        raise B.FeplbError("predictor_study needs at least one micro-batch for the history and one to measure")
     T = P * tokens_per_rank
     per = E // P
     hist = np.zeros(E, dtype=np.int64)
