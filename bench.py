@@ -175,6 +175,19 @@ def time_workload(name, steps, warmup, source_kind="device", fused_gather=True, 
                                   copy_gbps=nbytes / (ms["copy"] * 1e-3) / 1e9,
                                   wait_after_static_ms=ms["wait_for_copy"])
         res["moves"] = p.moves
+        # the host plan's latency on this machine's CPU (Section 2.3 budgets about 50 us on one core): both modes on the
+        # step's own counts, median of 200 calls through the C ABI
+        from paper_2604_19654_amd import binding as B
+        owner, flags = wl.owner(), wl.dyn_flags(4)
+        lat = {}
+        for mode_name, args in (("whole_expert_greedy", (64, B.PLAN_WHOLE, -1)), ("overflow_replicas", (0, B.PLAN_OVERFLOW, p.rank))):
+            ts = []
+            for _ in range(200):
+                t1 = time.perf_counter()
+                B.feplb_plan(wl.P, owner, p.counts, flags, p.slots, *args)
+                ts.append(time.perf_counter() - t1)
+            lat[mode_name] = float(np.median(ts)) * 1e6
+        res["plan_latency_us"] = lat
     res["pct_mfma_peak_ffn_kernels"] = 100.0 * res["ffn_tflops_kernels"] / MFMA_BF16_PEAK_TFLOPS
     res["reference_copy_gbps"] = _reference_copy_gbps(layer.buf.Y)
     res["reference_dense_gemm"] = _reference_dense_gemm(R, d, f, wl.X.device)
