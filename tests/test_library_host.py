@@ -279,3 +279,22 @@ def test_history_floor_and_predictor_error_codes():
     assert fe.feplb_straggler([3.0]) == 0.0
     L = fe.lib()
     assert L.feplb_straggler(0, None, None) == -1
+
+
+def test_a_missing_library_is_an_error_not_a_fallback(monkeypatch, tmp_path):
+    # the product path has no CPU fallback: without the built library every entry point raises
+    from paper_2604_19654_amd import binding
+    monkeypatch.setattr(binding, "_LIB", None)
+    monkeypatch.setattr(binding, "lib_path", lambda: str(tmp_path / "libfeplb.so"))
+    with pytest.raises(fe.FeplbError, match="is missing"):
+        binding.lib()
+    with pytest.raises(fe.FeplbError, match="is missing"):
+        fe.feplb_plan(2, [0, 1], [1, 1], [1, 1], [1, 1])
+    with pytest.raises(fe.FeplbError, match="is missing"):
+        fe.feplb_place(2, [1, 2], 1, [0, 1])
+    # and nothing in the package imports the oracle
+    import sys
+    import pathlib
+    pkg = pathlib.Path(binding.__file__).parent
+    for src in list(pkg.glob("*.py")) + list((pkg / "csrc").glob("*")):
+        assert "oracle" not in src.read_text(), src
